@@ -1,0 +1,151 @@
+/*
+ * bsa.h -- C ABI of the Bidirectional Sparse Attention (BSA) hot path for AMD MI355X (gfx950).
+ *
+ * One attention layer of a video diffusion transformer, sparsified in two directions
+ * (paper Sec. 3.2): queries that are redundant inside their 3D block are pruned
+ * (Sec. 3.2.2, Eq. 2) and every query block attends only to the minimal set of KV blocks
+ * whose pooled softmax mass reaches a threshold (Sec. 3.2.3, Eq. 4); exact softmax
+ * attention then runs over the survivors (Sec. 3.2.4, Eq. 5) and pruned positions are
+ * filled with their block center's output (Sec. 3.2.2, "Token Filling").
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers on the current HIP device unless stated.
+ *   - Q, K, V, O, dO, dQ, dK, dV are contiguous [B, H, L, d] in RASTER token order
+ *     n = t*Hs*Ws + h*Ws + w (Sec. 3.1), L = T*Hs*Ws; element type per shape.dtype.
+ *   - Blocks: (Ct, Ch, Cw) must divide (T, Hs, Ws) (Sec. 3.2.1).  Bk = Ct*Ch*Cw tokens
+ *     per block, N = L / Bk blocks, block id = (bt*Nh + bh)*Nw + bw, intra-block id
+ *     = (ct*Ch + ch)*Cw + cw.  "rows" = B*H*N (one row per head and query block).
+ *   - Ownership: the caller allocates and frees every buffer, including workspaces.
+ *     The library keeps no state and never allocates device memory.
+ *   - Asynchrony: a call only enqueues work on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream) and returns; it never synchronises.
+ *   - Errors: 0 on success, a negative bsa_status otherwise.  All argument checks are
+ *     done on the host before anything is launched; a failed call launches nothing.
+ *   - Determinism: equal inputs give bit-identical outputs (no floating-point atomics).
+ */
+#ifndef BSA_H_
+#define BSA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum bsa_dtype { BSA_F32 = 0, BSA_BF16 = 1 };
+
+enum bsa_status {
+  BSA_OK = 0,
+  BSA_ERR_NULL = -1,        /* a required pointer is NULL */
+  BSA_ERR_SHAPE = -2,       /* non-positive extent, block does not divide grid, unsupported d / Bk / N */
+  BSA_ERR_RANGE = -3,       /* threshold or keep ratio outside (0, 1], n_keep outside [1, Bk] */
+  BSA_ERR_CAPACITY = -4,    /* index buffer smaller than the worst case rows*N */
+  BSA_ERR_DTYPE = -5,       /* shape.dtype is neither BSA_F32 nor BSA_BF16 */
+  BSA_ERR_LAUNCH = -6,      /* the HIP runtime reported a launch error */
+  BSA_ERR_WORKSPACE = -7    /* workspace NULL or smaller than the *_workspace_bytes() figure */
+};
+
+typedef struct bsa_shape {
+  int32_t B, H;          /* batch, heads */
+  int32_t T, Hs, Ws;     /* latent grid (Sec. 3.1) */
+  int32_t Ct, Ch, Cw;    /* 3D block shape (Sec. 3.2.1) */
+  int32_t d;             /* head dimension, multiple of 8, <= 256 */
+  int32_t dtype;         /* enum bsa_dtype of Q/K/V/O and the gradients */
+} bsa_shape_t;
+
+/* Limits: Bk <= 256, N <= 8192, d % 8 == 0 and d <= 256. */
+
+const char* bsa_strerror(int status);
+
+/* Number of retained queries per block, ceil(keep_ratio * Bk) (Eq. 2); <0 on bad arguments. */
+int bsa_n_keep(const bsa_shape_t* shape, double keep_ratio);
+
+/*
+ * Block-level representations (Sec. 3.2.3): Xbar[b,h,i,:] = arithmetic mean of the Bk
+ * token vectors of block i, accumulated in fp64 in ascending intra-block order.
+ *   X    in   [B,H,L,d]  shape.dtype
+ *   Xbar out  [B,H,N,d]  double
+ */
+int bsa_pool_blocks(const bsa_shape_t* shape, const void* X, double* Xbar, void* stream);
+
+/*
+ * Sparse KV selection (Sec. 3.2.3, Eq. 4).  Block logits s_ij = score_scale * <Qbar_i, Kbar_j>
+ * (fp64, channel-ascending, multiply and add rounded separately).  For every row the
+ * blocks are ordered by (s descending, j ascending) and the shortest prefix whose
+ * softmax mass is >= threshold is kept (threshold >= 1 keeps all N).  Output is CSR:
+ *   q2k_ptr  out [rows+1] int32   q2k_ptr[r+1]-q2k_ptr[r] = number of KV blocks of row r
+ *                                 (the paper's q2k_num), q2k_ptr[rows] = nnz
+ *   q2k_idx  out [nnz]    int32   KV block ids of each row, ascending (the paper's q2k_index)
+ *   k2q_ptr / k2q_idx             the exact transpose per head: for row (b,h,j) the query
+ *                                 blocks i that list j, ascending.  Both NULL to skip.
+ *   nnz_dev  out int64 device scalar (may be NULL)
+ *   idx_capacity  number of int32 slots behind q2k_idx (and k2q_idx); must be >= rows*N,
+ *                 the data-independent worst case, else BSA_ERR_CAPACITY.
+ *   workspace     bsa_select_workspace_bytes(shape) bytes of device scratch.
+ * score_scale is normally 1/sqrt(d).
+ */
+size_t bsa_select_workspace_bytes(const bsa_shape_t* shape);
+int bsa_select_kv(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
+                  double threshold, double score_scale,
+                  int32_t* q2k_ptr, int32_t* q2k_idx, int64_t idx_capacity,
+                  int32_t* k2q_ptr, int32_t* k2q_idx, int64_t* nnz_dev,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sparse Query (Sec. 3.2.2, Eq. 2).  Per block: cosine similarity (fp64) of every token to
+ * the center token, local coordinate (Ct/2, Ch/2, Cw/2); the center plus the n_keep-1
+ * other tokens with the smallest cosine are retained (ties: lower intra-block id first;
+ * a zero vector has cosine 0).  n_keep = ceil(keep_ratio * Bk).
+ *   keep_idx out [B,H,N,n_keep] int32  intra-block ids, ascending
+ */
+int bsa_prune_q(const bsa_shape_t* shape, const void* Q, double keep_ratio,
+                int32_t* keep_idx, void* stream);
+
+/*
+ * Sparse attention forward with token filling (Eq. 5; Sec. 3.2.2 "Token Filling").
+ * Retained queries of block i attend, with exact softmax at scale sm_scale, to all Bk
+ * tokens of every KV block listed for row i; pruned positions receive the center's row.
+ *   O   out [B,H,L,d] shape.dtype,  LSE out [B,H,L] float (natural-log sum-exp, filled too)
+ * Every row must list at least one KV block (Eq. 4 always selects one).
+ * keep_idx rows must be ascending, distinct, in [0,Bk) and contain the center.
+ */
+int bsa_attn_fwd(const bsa_shape_t* shape, const void* Q, const void* K, const void* V,
+                 const int32_t* q2k_ptr, const int32_t* q2k_idx,
+                 const int32_t* keep_idx, int n_keep, float sm_scale,
+                 void* O, float* LSE, void* stream);
+
+/*
+ * Backward of bsa_attn_fwd with the index sets held constant (Sec. 3.3: the backward
+ * kernel reuses the forward's masks and mappings).  The fill copy back-propagates into
+ * the center row.  dQ rows of pruned queries and dK/dV of never-listed blocks are zero.
+ * dK/dV of a KV block are accumulated by one owner over its k2q list: no atomics.
+ *   O, LSE: the forward's outputs;  dO in [B,H,L,d];  dQ, dK, dV out [B,H,L,d]
+ *   workspace: bsa_bwd_workspace_bytes(shape, n_keep) bytes of device scratch.
+ */
+size_t bsa_bwd_workspace_bytes(const bsa_shape_t* shape, int n_keep);
+int bsa_attn_bwd(const bsa_shape_t* shape, const void* Q, const void* K, const void* V,
+                 const void* O, const float* LSE, const void* dO,
+                 const int32_t* q2k_ptr, const int32_t* q2k_idx,
+                 const int32_t* k2q_ptr, const int32_t* k2q_idx,
+                 const int32_t* keep_idx, int n_keep, float sm_scale,
+                 void* dQ, void* dK, void* dV,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Full (dense) softmax attention of Eq. 1 at the same shape, forward and backward: the
+ * baseline the sparse path is timed against.  Same layouts; the block fields of `shape`
+ * only fix the tile granularity (Bk) and must still divide the grid.
+ */
+size_t bsa_dense_bwd_workspace_bytes(const bsa_shape_t* shape);
+int bsa_dense_attn_fwd(const bsa_shape_t* shape, const void* Q, const void* K, const void* V,
+                       float sm_scale, void* O, float* LSE, void* stream);
+int bsa_dense_attn_bwd(const bsa_shape_t* shape, const void* Q, const void* K, const void* V,
+                       const void* O, const float* LSE, const void* dO, float sm_scale,
+                       void* dQ, void* dK, void* dV,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSA_H_ */

@@ -1,0 +1,97 @@
+// Internal definitions shared by the HIP translation units of libbsa (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bsa.h"
+
+namespace bsa {
+
+// Geometry of one call, derived on the host from bsa_shape_t and passed to kernels by value.
+struct Geom {
+  int B, H, T, Hs, Ws, Ct, Ch, Cw, d;
+  int Nt, Nh, Nw;  // blocks per axis
+  int Bk;          // tokens per block
+  int N;           // blocks per head
+  int L;           // tokens per head
+  int rows;        // B*H*N
+  int center;      // intra-block id of the critical token (Sec. 3.2.2)
+  int dense;       // 1: tiles are runs of Bk consecutive raster tokens (dense baseline)
+};
+
+// Raster index (Sec. 3.1) of intra-block token c of block i (Sec. 3.2.1).
+__host__ __device__ inline int token_of(const Geom& g, int i, int c) {
+  if (g.dense) return i * g.Bk + c;
+  const int bw = i % g.Nw, bh = (i / g.Nw) % g.Nh, bt = i / (g.Nw * g.Nh);
+  const int cw = c % g.Cw, ch = (c / g.Cw) % g.Ch, ct = c / (g.Cw * g.Ch);
+  return ((bt * g.Ct + ct) * g.Hs + (bh * g.Ch + ch)) * g.Ws + (bw * g.Cw + cw);
+}
+
+// Raster index of the first token (intra-block id 0) of block i.
+__host__ __device__ inline int block_origin(const Geom& g, int i) {
+  if (g.dense) return i * g.Bk;
+  const int bw = i % g.Nw, bh = (i / g.Nw) % g.Nh, bt = i / (g.Nw * g.Nh);
+  return ((bt * g.Ct) * g.Hs + bh * g.Ch) * g.Ws + bw * g.Cw;
+}
+
+// Offset of intra-block token c from the block origin, in tokens.
+__host__ __device__ inline int intra_offset(const Geom& g, int c) {
+  if (g.dense) return c;
+  const int cw = c % g.Cw, ch = (c / g.Cw) % g.Ch, ct = c / (g.Cw * g.Ch);
+  return (ct * g.Hs + ch) * g.Ws + cw;
+}
+
+int make_geom(const bsa_shape_t* s, Geom* g);  // validates; returns bsa_status
+
+inline int check_launch() {
+  return hipGetLastError() == hipSuccess ? BSA_OK : BSA_ERR_LAUNCH;
+}
+
+// bf16 <-> fp32 (round to nearest even), bit-level.
+__device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ inline uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ inline float load_f32(const T* p);
+template <> __device__ inline float load_f32<float>(const float* p) { return *p; }
+template <> __device__ inline float load_f32<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
+template <typename T> __device__ inline void store_f32(T* p, float v);
+template <> __device__ inline void store_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ inline void store_f32<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// ---- entry points implemented per translation unit (all enqueue on `st`) ----
+int launch_pool(const Geom& g, int dtype, const void* X, double* Xbar, hipStream_t st);
+int launch_prune(const Geom& g, int dtype, const void* Q, int n_keep, int32_t* keep_idx, hipStream_t st);
+size_t select_workspace_bytes(const Geom& g);
+int launch_select(const Geom& g, const double* Qbar, const double* Kbar, double threshold,
+                  double score_scale, int32_t* q2k_ptr, int32_t* q2k_idx, int32_t* k2q_ptr,
+                  int32_t* k2q_idx, int64_t* nnz_dev, void* ws, hipStream_t st);
+
+struct AttnArgs {
+  const void *Q, *K, *V, *O, *dO;
+  const float* LSE_in;
+  const int32_t *q2k_ptr, *q2k_idx, *k2q_ptr, *k2q_idx, *keep_idx;
+  int n_keep;
+  float sm_scale;
+  void *O_out, *dQ, *dK, *dV;
+  float* LSE_out;
+  void* ws;
+};
+
+// plain-ALU fp32-accumulate kernels: any supported shape, fp32 or bf16 storage
+int launch_fwd_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st);
+int launch_bwd_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st);
+size_t bwd_workspace_generic(const Geom& g, int n_keep);
+
+// bf16 MFMA kernels: Bk == 64, d == 128 (or 64), n_keep <= 64
+bool mfma_supported(const Geom& g, int dtype, int n_keep);
+int launch_fwd_mfma(const Geom& g, const AttnArgs& a, hipStream_t st);
+int launch_bwd_mfma(const Geom& g, const AttnArgs& a, hipStream_t st);
+size_t bwd_workspace_mfma(const Geom& g, int n_keep);
+
+}  // namespace bsa

@@ -1,0 +1,98 @@
+"""Helpers for the GPU parity tests: move seeded workloads to the device, run the C-ABI
+path through the binding, run the CPU oracle per head, compare."""
+from __future__ import annotations
+
+from math import sqrt
+from typing import Dict, Iterable, Optional
+
+import numpy as np
+import torch
+
+from bsa_workloads import Workload, head_inputs, head_tensor
+from oracle import bsa_oracle as o
+from paper_2509_01085_amd import binding as B
+
+# Deciding comparisons closer to equality than this (relative to the row's total mass) are
+# within reach of the one non-reproducible step (exp of libm vs the device, summation tree
+# of the scan): such a row may legitimately differ by its boundary block.
+SELECT_MARGIN = 1e-10
+
+
+def shape_of(wl: Workload) -> B.Shape:
+    return B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16)
+
+
+def part_of(wl: Workload) -> o.Partition:
+    return o.Partition(*wl.grid, *wl.block)
+
+
+def device_inputs(wl: Workload, names=("Q", "K", "V", "dO"), heads: Optional[Iterable[int]] = None) -> Dict[str, torch.Tensor]:
+    """[B,H,L,d] device tensors of the workload's dtype (heads not listed stay zero)."""
+    dt = torch.float32 if wl.dtype == "fp32" else torch.bfloat16
+    out = {}
+    for name in names:
+        host = torch.zeros((wl.B, wl.H, wl.L, wl.d), dtype=dt)
+        for b in range(wl.B):
+            for h in (range(wl.H) if heads is None else heads):
+                host[b, h] = torch.from_numpy(head_tensor(wl, name, b, h)).to(dt)  # exact: values are bf16 already
+        out[name] = host.cuda()
+    return out
+
+
+def run_indices(wl: Workload, x: Dict[str, torch.Tensor], threshold=None, keep_ratio=None):
+    shp = shape_of(wl)
+    Qbar = B.pool_blocks(shp, x["Q"])
+    Kbar = B.pool_blocks(shp, x["K"])
+    lists = B.select_kv(shp, Qbar, Kbar, wl.threshold if threshold is None else threshold)
+    keep = B.prune_q(shp, x["Q"], wl.keep_ratio if keep_ratio is None else keep_ratio)
+    return shp, Qbar, Kbar, lists, keep
+
+
+def lists_to_host(shp: B.Shape, lists: B.KvLists):
+    torch.cuda.synchronize()
+    nnz = int(lists.nnz.item())
+    q2k_ptr = lists.q2k_ptr.cpu().numpy()
+    assert q2k_ptr[-1] == nnz
+    return dict(q2k_ptr=q2k_ptr, q2k_idx=lists.q2k_idx[:nnz].cpu().numpy(),
+                k2q_ptr=lists.k2q_ptr.cpu().numpy(), k2q_idx=lists.k2q_idx[:nnz].cpu().numpy(), nnz=nnz)
+
+
+def head_csr(host: dict, shp: B.Shape, b: int, h: int, which="q2k"):
+    """Slice one head's CSR out of the all-rows CSR, rebased to start at 0."""
+    r0 = (b * shp.H + h) * shp.N
+    ptr = host[which + "_ptr"][r0:r0 + shp.N + 1]
+    return (ptr - ptr[0]).astype(np.int32), host[which + "_idx"][ptr[0]:ptr[-1]]
+
+
+def check_lists_against_oracle(wl: Workload, shp: B.Shape, host: dict, b: int, h: int, ix: o.HeadResult, scores=None):
+    """Bit-exact CSR and transposed CSR; a row may differ only if its margin is below SELECT_MARGIN."""
+    ptr, idx = head_csr(host, shp, b, h, "q2k")
+    if np.array_equal(ptr, ix.q2k_ptr) and np.array_equal(idx, ix.q2k_idx):
+        tptr, tidx = head_csr(host, shp, b, h, "k2q")
+        assert np.array_equal(tptr, ix.k2q_ptr) and np.array_equal(tidx, ix.k2q_idx)
+        return 0
+    assert scores is not None, "lists differ from the oracle"
+    bad = 0
+    for i in range(shp.N):
+        mine = idx[ptr[i]:ptr[i + 1]]
+        ref = ix.q2k_idx[ix.q2k_ptr[i]:ix.q2k_ptr[i + 1]]
+        if not np.array_equal(mine, ref):
+            sel = o.select_row(scores[i], wl.threshold)
+            assert sel.margin < SELECT_MARGIN, (i, sel.margin)
+            assert abs(len(mine) - len(ref)) == 1 and len(np.setxor1d(mine, ref)) == 1
+            bad += 1
+    return bad
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max |got - ref| / RMS(ref): the tolerance metric of the parity bar."""
+    rms = float(np.sqrt(np.mean(np.asarray(ref, dtype=np.float64) ** 2)))
+    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(rms, 1e-30))
+
+
+def tol_of(wl: Workload) -> float:
+    return 1e-4 if wl.dtype == "fp32" else 2e-2
+
+
+def host_f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
