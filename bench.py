@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the BSA hot path on one MI355X.
+
+A step is one attention layer, forward + backward, through all five C-ABI calls
+(pool Q, pool K, select, prune, attention fwd, attention bwd) on a seeded synthetic
+video-shaped workload that is resident in HBM before the timed region starts.
+
+Prints ONE JSON line: ms per layer (the headline metric, lower is better), effective
+(dense-equivalent) and actual TFLOP/s, the roofline of the dominant kernel measured live
+with events on the launch stream, the in-repo dense baseline at the same shape, and the CPU
+oracle timed on this host's cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+from math import sqrt
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="wan1p3b", help="tiny | wan1p3b | hd720p | long")
+    ap.add_argument("--sigma", type=float, default=None)
+    ap.add_argument("--threshold", type=float, default=None)
+    ap.add_argument("--keep-ratio", type=float, default=None)
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-heads", type=int, default=1, help="heads of the workload the CPU oracle is timed on")
+    return ap.parse_args()
+
+
+def make_inputs(wl, torch):
+    from bsa_workloads import TENSOR_NAMES, head_tensor
+
+    dt = torch.float32 if wl.dtype == "fp32" else torch.bfloat16
+    jobs = [(n, b, h) for n in TENSOR_NAMES for b in range(wl.B) for h in range(wl.H)]
+    host = {n: torch.empty((wl.B, wl.H, wl.L, wl.d), dtype=dt, pin_memory=True) for n in TENSOR_NAMES}
+
+    def one(job):
+        n, b, h = job
+        host[n][b, h] = torch.from_numpy(head_tensor(wl, n, b, h)).to(dt)
+
+    with ThreadPoolExecutor(max_workers=min(16, len(os.sched_getaffinity(0)))) as ex:
+        list(ex.map(one, jobs))
+    return {n: t.cuda() for n, t in host.items()}
+
+
+def timed(torch, fn, iters):
+    """Average ms per call of fn over `iters` calls, events on the current (launch) stream."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def cpu_baseline(wl, heads: int):
+    """The oracle as it stands, on this host's cores: `heads` heads of the same workload."""
+    import numpy as np
+
+    from bsa_workloads import head_inputs
+    from oracle import bsa_oracle as o
+
+    part = o.Partition(*wl.grid, *wl.block)
+    dtype = np.float64 if wl.L <= 4096 else np.float32  # attention GEMMs; decisions are always fp64
+    t = 0.0
+    for h in range(heads):
+        x = head_inputs(wl, 0, h)
+        t0 = time.perf_counter()
+        o.bsa_head(x["Q"], x["K"], x["V"], x["dO"], part, wl.threshold, wl.keep_ratio, dtype=dtype)
+        t += time.perf_counter() - t0
+    per_layer_ms = t / heads * wl.B * wl.H * 1e3
+    return {
+        "value": per_layer_ms, "unit": "ms/layer (fwd+bwd)", "cores": len(os.sched_getaffinity(0)), "kind": "oracle",
+        "sample": f"{heads} of {wl.B * wl.H} heads timed ({t:.1f} s), scaled by heads (heads are independent); "
+                  f"attention GEMMs in {np.dtype(dtype).name}",
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from bsa_workloads import WORKLOADS
+    from paper_2509_01085_amd import binding as B
+
+    wl = WORKLOADS[args.workload]
+    over = {k: v for k, v in (("sigma", args.sigma), ("threshold", args.threshold), ("keep_ratio", args.keep_ratio)) if v is not None}
+    if over:
+        wl = wl.replace(**over)
+    shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    x = make_inputs(wl, torch)
+    Q, K, V, dO = x["Q"], x["K"], x["V"], x["dO"]
+
+    # every output and workspace is allocated once, outside the timed region
+    nk = B.n_keep(shp, wl.keep_ratio)
+    Qbar = torch.empty((wl.B, wl.H, shp.N, wl.d), dtype=torch.float64, device=dev)
+    Kbar = torch.empty_like(Qbar)
+    lists = B.alloc_kv_lists(shp, dev)
+    keep = torch.empty((wl.B, wl.H, shp.N, nk), dtype=torch.int32, device=dev)
+    O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    LSE = torch.empty((wl.B, wl.H, wl.L), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(1, B.bwd_workspace_bytes(shp, nk)), dtype=torch.uint8, device=dev)
+
+    def indices():
+        B.pool_blocks(shp, Q, Qbar)
+        B.pool_blocks(shp, K, Kbar)
+        B.select_kv(shp, Qbar, Kbar, wl.threshold, out=lists)
+        B.prune_q(shp, Q, wl.keep_ratio, keep)
+
+    def fwd():
+        B.attn_fwd(shp, Q, K, V, lists, keep, O=O, LSE=LSE)
+
+    def bwd():
+        B.attn_bwd(shp, Q, K, V, O, LSE, dO, lists, keep, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+
+    def step():
+        indices()
+        fwd()
+        bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms_step = timed(torch, step, args.steps)
+    wall = time.perf_counter() - t0
+
+    # per-call breakdown (same buffers, separate event brackets)
+    parts = {
+        "pool_q": timed(torch, lambda: B.pool_blocks(shp, Q, Qbar), args.steps),
+        "pool_k": timed(torch, lambda: B.pool_blocks(shp, K, Kbar), args.steps),
+        "select": timed(torch, lambda: B.select_kv(shp, Qbar, Kbar, wl.threshold, out=lists), args.steps),
+        "prune": timed(torch, lambda: B.prune_q(shp, Q, wl.keep_ratio, keep), args.steps),
+        "attn_fwd": timed(torch, fwd, args.steps),
+        "attn_bwd": timed(torch, bwd, args.steps),
+    }
+    nnz = int(lists.nnz.item())
+    f = nnz / (shp.rows * shp.N)
+    pair_flops = wl.d * nk * shp.Bk * nnz  # x4 fwd, x10 bwd (FlashAttention convention: one S recompute)
+    t_attn = parts["attn_fwd"] + parts["attn_bwd"]
+    actual_tflops = 14 * pair_flops / (t_attn * 1e-3) / 1e12
+    dense_flops = 14.0 * wl.B * wl.H * wl.L * wl.L * wl.d
+    fwd_tflops = 4 * pair_flops / (parts["attn_fwd"] * 1e-3) / 1e12
+    bwd_tflops = 10 * pair_flops / (parts["attn_bwd"] * 1e-3) / 1e12
+
+    out = {
+        "metric": "bsa_fwd_bwd_ms_per_layer", "value": ms_step, "unit": "ms", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "d": wl.d, "grid": list(wl.grid), "block": list(wl.block),
+                   "tokens": wl.L, "threshold": wl.threshold, "keep_ratio": wl.keep_ratio, "sigma": wl.sigma},
+        "selected_block_fraction": f, "nnz": nnz, "n_keep": nk,
+        "ms_per_call": parts,
+        "effective_tflops": dense_flops / (ms_step * 1e-3) / 1e12,
+        "actual_tflops": actual_tflops,
+        "actual_pct_of_bf16_peak": 100.0 * actual_tflops / PEAK_BF16_TFLOPS,
+        "roofline": {"kernel": "attn_bwd (pre + dQ + dK/dV)", "bound": "mfma", "achieved": bwd_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": bwd_tflops / PEAK_BF16_TFLOPS, "traffic": None},
+        "roofline_fwd": {"kernel": "fwd_mfma_kernel", "bound": "mfma", "achieved": fwd_tflops, "peak": PEAK_BF16_TFLOPS,
+                         "unit": "TFLOP/s", "frac": fwd_tflops / PEAK_BF16_TFLOPS, "traffic": None},
+        "wall_s_timed_region": wall,
+    }
+    pool_bytes = 2 * Q.numel() * Q.element_size() + 2 * Qbar.numel() * 8 + keep.numel() * 4 + Q.numel() * Q.element_size()
+    t_stream = parts["pool_q"] + parts["pool_k"] + parts["prune"]
+    out["index_prep_hbm"] = {"bytes": pool_bytes, "achieved_GBs": pool_bytes / (t_stream * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS}
+
+    if not args.no_dense and wl.L <= 40000:
+        dws = torch.empty(max(1, B.dense_bwd_workspace_bytes(shp)), dtype=torch.uint8, device=dev)
+        Od, LSEd = torch.empty_like(Q), torch.empty_like(LSE)
+        dfw = lambda: B.dense_attn_fwd(shp, Q, K, V, O=Od, LSE=LSEd)
+        dbw = lambda: B.dense_attn_bwd(shp, Q, K, V, Od, LSEd, dO, dQ=dQ, dK=dK, dV=dV, workspace=dws)
+        dfw(); dbw()
+        n = max(1, min(3, args.steps))
+        td_f, td_b = timed(torch, dfw, n), timed(torch, dbw, n)
+        out["dense_baseline"] = {"fwd_ms": td_f, "bwd_ms": td_b, "ms": td_f + td_b,
+                                 "tflops": dense_flops / ((td_f + td_b) * 1e-3) / 1e12,
+                                 "speedup_of_bsa": (td_f + td_b) / ms_step}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, max(1, min(args.cpu_heads, wl.H)))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -336,14 +336,18 @@ def folded_grad(dO: np.ndarray, part: Partition, keep_idx, i: int, tok=None) -> 
 
 
 def attn_bwd(Q, K, V, dO, part: Partition, q2k_ptr, q2k_idx, keep_idx, sm_scale: float,
-             dtype=np.float64, q_blocks: Optional[Sequence[int]] = None):
+             dtype=np.float64, q_blocks: Optional[Sequence[int]] = None, O_in=None):
     """dQ, dK, dV for one head.
 
     With P = softmax(sm_scale * q k^T) over the selected keys, o = P v and g the
     folded upstream gradient:  delta_n = <g_n, o_n>;  dV += P^T g;
     dS = P * (g v^T - delta);  dQ = sm_scale * dS k;  dK += sm_scale * dS^T q.
     Rows of pruned queries get dQ = 0.  If `q_blocks` is given, only those
-    query blocks contribute (dK/dV are then partial sums)."""
+    query blocks contribute (dK/dV are then partial sums).
+
+    `O_in` [L, d]: the forward output as a caller stored it (possibly rounded to
+    the storage type).  A backward entry point receives O as an argument, and
+    delta is then formed from that stored O; None means the exact o."""
     tok = part.block_tokens()
     Q = np.asarray(Q, dtype=dtype)
     K = np.asarray(K, dtype=dtype)
@@ -357,6 +361,8 @@ def attn_bwd(Q, K, V, dO, part: Partition, q2k_ptr, q2k_idx, keep_idx, sm_scale:
         keys = tok[q2k_idx[q2k_ptr[i]:q2k_ptr[i + 1]]].reshape(-1)
         q, k, v = Q[rows], K[keys], V[keys]
         o, _, P = attend_block(q, k, v, sm_scale)
+        if O_in is not None:
+            o = np.asarray(O_in, dtype=dtype)[rows]
         g = folded_grad(dO, part, keep_idx, i, tok)
         delta = (g * o).sum(axis=1, keepdims=True)
         dS = P * (g @ v.T - delta)
@@ -367,7 +373,7 @@ def attn_bwd(Q, K, V, dO, part: Partition, q2k_ptr, q2k_idx, keep_idx, sm_scale:
 
 
 def attn_bwd_kv_block(Q, K, V, dO, part: Partition, q2k_ptr, q2k_idx, k2q_ptr, k2q_idx,
-                      keep_idx, sm_scale: float, j: int, dtype=np.float64):
+                      keep_idx, sm_scale: float, j: int, dtype=np.float64, O_in=None):
     """dK, dV of the Bk tokens of KV block j alone (sum over the query blocks that list j)."""
     tok = part.block_tokens()
     Q = np.asarray(Q, dtype=dtype)
@@ -382,6 +388,8 @@ def attn_bwd_kv_block(Q, K, V, dO, part: Partition, q2k_ptr, q2k_idx, k2q_ptr, k
         keys = tok[q2k_idx[q2k_ptr[i]:q2k_ptr[i + 1]]].reshape(-1)
         q = Q[rows]
         o, lse, _ = attend_block(q, K[keys], V[keys], sm_scale)
+        if O_in is not None:
+            o = np.asarray(O_in, dtype=dtype)[rows]
         g = folded_grad(dO, part, keep_idx, int(i), tok)
         delta = (g * o).sum(axis=1, keepdims=True)
         Pj = np.exp((q @ kj.T) * dtype(sm_scale) - lse[:, None])
@@ -421,10 +429,14 @@ def bsa_indices(Q, K, part: Partition, threshold: float, keep_ratio: float,
 
 
 def bsa_head(Q, K, V, dO, part: Partition, threshold: float, keep_ratio: float,
-             sm_scale: Optional[float] = None, dtype=np.float64):
-    """Full fwd+bwd of one head.  Returns (indices, O, LSE, dQ, dK, dV)."""
+             sm_scale: Optional[float] = None, dtype=np.float64, o_storage=None):
+    """Full fwd+bwd of one head.  Returns (indices, O, LSE, dQ, dK, dV).
+
+    `o_storage`: optional function modelling how O is stored between the two
+    passes (e.g. rounding to bfloat16); the backward then reads that stored O."""
     sm_scale = 1.0 / sqrt(Q.shape[1]) if sm_scale is None else sm_scale
     ix = bsa_indices(Q, K, part, threshold, keep_ratio)
     O, LSE = attn_fwd(Q, K, V, part, ix.q2k_ptr, ix.q2k_idx, ix.keep_idx, sm_scale, dtype)
-    dQ, dK, dV = attn_bwd(Q, K, V, dO, part, ix.q2k_ptr, ix.q2k_idx, ix.keep_idx, sm_scale, dtype)
+    O_in = None if o_storage is None else o_storage(O)
+    dQ, dK, dV = attn_bwd(Q, K, V, dO, part, ix.q2k_ptr, ix.q2k_idx, ix.keep_idx, sm_scale, dtype, O_in=O_in)
     return ix, O, LSE, dQ, dK, dV

@@ -1,0 +1,76 @@
+// Building blocks of the bf16 MFMA attention kernels (gfx950, wave64).
+//
+// Matrix-core instruction used throughout: v_mfma_f32_32x32x16_bf16, D[32x32] += A[32x16] B[16x32].
+// Register layouts (lane l, g = l / 32, c = l % 32):
+//   A: lane holds row i = c,    k = 8g + t (t = 0..7, one 16-byte fragment)
+//   B: lane holds column j = c, k = 8g + t
+//   D: lane holds column j = c, rows i = 8*(r/4) + 4g + r%4 for register r = 0..15
+// All kernels keep the QUERY index on the D column, so a softmax row lives in one lane pair
+// (l, l^32) and its statistics need a single cross-lane exchange.
+//
+// A D tile becomes the B operand of the next contraction without any shuffle: registers
+// 8h..8h+7 of lane group g hold rows {16h + 8(t/4) + 4g + t%4}, which is read as "k slot
+// (g, t) of k-step h".  The matching A operand must then present the same rows in the same
+// slots, so tiles that play that A role are stored in LDS with their 64 contraction indices
+// permuted by slot_pos(): the 8 indices of one (k-step, lane group) are contiguous 16 bytes.
+#pragma once
+
+#include "bsa_common.h"
+
+namespace bsa {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Position, inside a row of 64 contraction indices, of index x (see file comment).
+__host__ __device__ constexpr int slot_pos(int x) {
+  return (x & ~15) | (((x >> 2) & 1) << 3) | (((x >> 3) & 1) << 2) | (x & 3);
+}
+
+__device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ inline bf16x8 lds_frag(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+__device__ inline bf16x8 as_frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// registers 8h..8h+7 of a D tile -> one bf16 B-operand fragment
+__device__ inline bf16x8 d_to_b(const f32x16& d, int h) {
+  u32x4 v;
+  v.x = pack_bf16(d[8 * h + 0], d[8 * h + 1]);
+  v.y = pack_bf16(d[8 * h + 2], d[8 * h + 3]);
+  v.z = pack_bf16(d[8 * h + 4], d[8 * h + 5]);
+  v.w = pack_bf16(d[8 * h + 6], d[8 * h + 7]);
+  return as_frag(v);
+}
+
+__device__ inline float xor32(float v) { return __shfl_xor(v, 32); }
+
+// Transpose a 4 (rows) x 8 (columns) block of bf16 held as four 16-byte rows; out[c] packs
+// column c's four values (row 0 in the low half of .x).
+__device__ inline void transpose_4x8(const u32x4 (&r)[4], u32x2 (&out)[8]) {
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const uint32_t a = r[0][m], b = r[1][m], c = r[2][m], d = r[3][m];
+    out[2 * m].x = (a & 0xffffu) | (b << 16);
+    out[2 * m].y = (c & 0xffffu) | (d << 16);
+    out[2 * m + 1].x = (a >> 16) | (b & 0xffff0000u);
+    out[2 * m + 1].y = (c >> 16) | (d & 0xffff0000u);
+  }
+}
+
+}  // namespace bsa

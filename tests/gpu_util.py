@@ -8,7 +8,7 @@ from typing import Dict, Iterable, Optional
 import numpy as np
 import torch
 
-from bsa_workloads import Workload, head_inputs, head_tensor
+from bsa_workloads import Workload, bf16_round, head_inputs, head_tensor
 from oracle import bsa_oracle as o
 from paper_2509_01085_amd import binding as B
 
@@ -85,9 +85,59 @@ def check_lists_against_oracle(wl: Workload, shp: B.Shape, host: dict, b: int, h
 
 
 def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
-    """max |got - ref| / RMS(ref): the tolerance metric of the parity bar."""
+    """max |got - ref| / RMS(ref): the plain tolerance metric."""
     rms = float(np.sqrt(np.mean(np.asarray(ref, dtype=np.float64) ** 2)))
     return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(rms, 1e-30))
+
+
+def abs_contractions(xi: dict, part: o.Partition, ix, sm_scale: float, q_blocks=None):
+    """A_X = the contraction that produces X with every term replaced by its absolute value
+    (X in O, dQ, dK, dV): the first-order bound on what rounding the operands of that
+    contraction can do is (relative operand error) * A_X, element by element."""
+    tok = part.block_tokens()
+    X = {k: np.asarray(v, dtype=np.float64) for k, v in xi.items()}
+    A = {k: np.zeros((part.L, X["Q"].shape[1])) for k in ("O", "dQ", "dK", "dV")}
+    for i in (range(part.N) if q_blocks is None else q_blocks):
+        rows = tok[i, ix.keep_idx[i]]
+        keys = tok[ix.q2k_idx[ix.q2k_ptr[i]:ix.q2k_ptr[i + 1]]].reshape(-1)
+        q, k, v = X["Q"][rows], X["K"][keys], X["V"][keys]
+        out, _, P = o.attend_block(q, k, v, sm_scale)
+        g = o.folded_grad(X["dO"], part, ix.keep_idx, i, tok)
+        dS = P * (g @ v.T - (g * out).sum(axis=1, keepdims=True))
+        aO = P @ np.abs(v)
+        cpos = int(np.nonzero(ix.keep_idx[i] == part.center)[0][0])
+        A["O"][tok[i]] = aO[cpos]
+        A["O"][rows] = aO
+        A["dQ"][rows] = sm_scale * (np.abs(dS) @ np.abs(k))
+        A["dK"][keys] += sm_scale * (np.abs(dS).T @ np.abs(q))
+        A["dV"][keys] += P.T @ np.abs(g)
+    return A
+
+
+BF16_ULP = 2.0 ** -7
+
+
+def parity_excess(got: np.ndarray, ref: np.ndarray, dtype: str, A: Optional[np.ndarray] = None) -> float:
+    """The parity figure compared with the tolerance (1e-4 for fp32, 2e-2 for bf16).
+
+    fp32: max |got - ref| / RMS(ref).
+    bf16: max (|got - ref| - 2^-7 * A) / RMS(ref), A from abs_contractions(): one bf16 ulp of
+    the absolute contraction covers the storage rounding of the result (|ref| <= A, half an
+    ulp) and the rounding of the two bf16 operands of each product (half an ulp each)."""
+    got = np.asarray(got, dtype=np.float64)
+    rms = max(float(np.sqrt(np.mean(np.asarray(ref, dtype=np.float64) ** 2))), 1e-30)
+    err = np.abs(got - ref)
+    if dtype == "bf16":
+        assert A is not None
+        err = np.maximum(err - BF16_ULP * A, 0.0)
+    return float(err.max() / rms)
+
+
+def o_storage_of(wl: Workload):
+    """How the forward output is stored before the backward reads it back (None: exactly)."""
+    if wl.dtype == "fp32":
+        return lambda O: np.asarray(O, dtype=np.float32)
+    return lambda O: bf16_round(np.asarray(O, dtype=np.float32))
 
 
 def tol_of(wl: Workload) -> float:

@@ -363,3 +363,19 @@ def test_generator_is_seeded_and_bf16_exact():
         assert np.array_equal(a[k].view(np.uint32) & 0xFFFF, np.zeros_like(a[k], dtype=np.uint32))
     assert 1.2 < a["Q"].std() < 1.8  # four unit sinusoids (var 2) + noise 0.09
     assert 0.9 < a["dO"].std() < 1.1
+
+
+def test_backward_with_stored_output_equals_exact_backward_when_storage_is_exact():
+    part = tiny_part()
+    x = tiny_inputs()
+    scale = 1 / sqrt(TINY.d)
+    ix = o.bsa_indices(x["Q"], x["K"], part, 0.6, 0.5)
+    args = (part, ix.q2k_ptr, ix.q2k_idx, ix.keep_idx, scale)
+    O, _ = o.attn_fwd(x["Q"], x["K"], x["V"], *args)
+    exact = o.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], *args)
+    stored = o.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], *args, O_in=O)
+    for a, b in zip(exact, stored):
+        assert np.abs(a - b).max() < 1e-13
+    # a perturbed stored O changes dQ and dK through delta only, never dV
+    bumped = o.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], *args, O_in=O + 1e-3)
+    assert np.array_equal(bumped[2], exact[2]) and np.abs(bumped[0] - exact[0]).max() > 1e-6
