@@ -90,13 +90,27 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(rms, 1e-30))
 
 
-def abs_contractions(xi: dict, part: o.Partition, ix, sm_scale: float, q_blocks=None):
-    """A_X = the contraction that produces X with every term replaced by its absolute value
-    (X in O, dQ, dK, dV): the first-order bound on what rounding the operands of that
-    contraction can do is (relative operand error) * A_X, element by element."""
+BF16_U = 2.0 ** -8  # unit roundoff of bfloat16 (8 significant bits, round to nearest even)
+
+
+def rounding_bounds(xi: dict, part: o.Partition, ix, sm_scale: float, q_blocks=None):
+    """First-order bounds E_X (X in O, dQ, dK, dV), element by element, on what storing
+    the intermediate operands in bfloat16 can do to X.  With u = 2^-8:
+
+      g  (folded upstream gradient) is rounded before it enters a contraction: |dg| <= u |g|
+         hence |d(dP)| <= u |g| |v|^T
+      P  is rounded before P v and P^T g:                  |dP~| <= u P
+      dS = P (dP - delta) is rounded before dS k, dS^T q:  |d(dS)| <= P u |g||v|^T + u |dS|
+
+      E_O  = u P |v|              E_dV = 2u P^T |g|
+      E_dQ = scale |d(dS)| |k|    E_dK = scale |d(dS)|^T |q|
+
+    Q, K, V, dO are exact in both implementations and accumulation is fp32 or better.
+    The rounding of the stored result itself, u |X|, is added by parity_excess()."""
+    u = BF16_U
     tok = part.block_tokens()
     X = {k: np.asarray(v, dtype=np.float64) for k, v in xi.items()}
-    A = {k: np.zeros((part.L, X["Q"].shape[1])) for k in ("O", "dQ", "dK", "dV")}
+    E = {k: np.zeros((part.L, X["Q"].shape[1])) for k in ("O", "dQ", "dK", "dV")}
     for i in (range(part.N) if q_blocks is None else q_blocks):
         rows = tok[i, ix.keep_idx[i]]
         keys = tok[ix.q2k_idx[ix.q2k_ptr[i]:ix.q2k_ptr[i + 1]]].reshape(-1)
@@ -104,32 +118,30 @@ def abs_contractions(xi: dict, part: o.Partition, ix, sm_scale: float, q_blocks=
         out, _, P = o.attend_block(q, k, v, sm_scale)
         g = o.folded_grad(X["dO"], part, ix.keep_idx, i, tok)
         dS = P * (g @ v.T - (g * out).sum(axis=1, keepdims=True))
-        aO = P @ np.abs(v)
+        ddS = u * (P * (np.abs(g) @ np.abs(v).T) + np.abs(dS))
+        eO = u * (P @ np.abs(v))
         cpos = int(np.nonzero(ix.keep_idx[i] == part.center)[0][0])
-        A["O"][tok[i]] = aO[cpos]
-        A["O"][rows] = aO
-        A["dQ"][rows] = sm_scale * (np.abs(dS) @ np.abs(k))
-        A["dK"][keys] += sm_scale * (np.abs(dS).T @ np.abs(q))
-        A["dV"][keys] += P.T @ np.abs(g)
-    return A
+        E["O"][tok[i]] = eO[cpos]
+        E["O"][rows] = eO
+        E["dQ"][rows] = sm_scale * (ddS @ np.abs(k))
+        E["dK"][keys] += sm_scale * (ddS.T @ np.abs(q))
+        E["dV"][keys] += 2 * u * (P.T @ np.abs(g))
+    return E
 
 
-BF16_ULP = 2.0 ** -7
-
-
-def parity_excess(got: np.ndarray, ref: np.ndarray, dtype: str, A: Optional[np.ndarray] = None) -> float:
+def parity_excess(got: np.ndarray, ref: np.ndarray, dtype: str, E: Optional[np.ndarray] = None) -> float:
     """The parity figure compared with the tolerance (1e-4 for fp32, 2e-2 for bf16).
 
     fp32: max |got - ref| / RMS(ref).
-    bf16: max (|got - ref| - 2^-7 * A) / RMS(ref), A from abs_contractions(): one bf16 ulp of
-    the absolute contraction covers the storage rounding of the result (|ref| <= A, half an
-    ulp) and the rounding of the two bf16 operands of each product (half an ulp each)."""
+    bf16: max (|got - ref| - E - u |ref|) / RMS(ref), E from rounding_bounds(): what is left
+    after the unavoidable effect of bfloat16 storage of operands and of the result must
+    stay below the tolerance."""
     got = np.asarray(got, dtype=np.float64)
     rms = max(float(np.sqrt(np.mean(np.asarray(ref, dtype=np.float64) ** 2))), 1e-30)
     err = np.abs(got - ref)
     if dtype == "bf16":
-        assert A is not None
-        err = np.maximum(err - BF16_ULP * A, 0.0)
+        assert E is not None
+        err = np.maximum(err - E - BF16_U * np.abs(ref), 0.0)
     return float(err.max() / rms)
 
 

@@ -58,7 +58,7 @@ def run_case(name: str):
             ref[b, h] = o.bsa_head(xi["Q"], xi["K"], xi["V"], xi["dO"], part, wl.threshold, wl.keep_ratio,
                                    o_storage=U.o_storage_of(wl))
             if wl.dtype == "bf16":
-                bound[b, h] = U.abs_contractions(xi, part, ref[b, h][0], 1 / sqrt(wl.d))
+                bound[b, h] = U.rounding_bounds(xi, part, ref[b, h][0], 1 / sqrt(wl.d))
     return dict(wl=wl, shp=shp, part=part, x=x, Qbar=Qbar, Kbar=Kbar, lists=lists, host=host, keep=keep,
                 O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV, ref=ref, bound=bound)
 
@@ -159,7 +159,7 @@ def test_dense_baseline_is_full_attention(name):
         xi = head_inputs(wl, b, h)
         ix, rO, rL, rdQ, rdK, rdV = o.bsa_head(xi["Q"], xi["K"], xi["V"], xi["dO"], r["part"], 1.0, 1.0,
                                                o_storage=U.o_storage_of(wl))
-        A = U.abs_contractions(xi, r["part"], ix, 1 / sqrt(wl.d)) if wl.dtype == "bf16" else {}
+        A = U.rounding_bounds(xi, r["part"], ix, 1 / sqrt(wl.d)) if wl.dtype == "bf16" else {}
         assert np.abs(U.host_f64(LSE[b, h]) - rL).max() < (1e-4 if wl.dtype == "fp32" else 2e-2)
         for name, got, ref in (("O", O, rO), ("dQ", dQ, rdQ), ("dK", dK, rdK), ("dV", dV, rdV)):
             assert U.parity_excess(U.host_f64(got[b, h]), ref, wl.dtype, A.get(name)) < tol, name
