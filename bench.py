@@ -133,8 +133,8 @@ def main():
     def fwd():
         B.attn_fwd(shp, Q, K, V, lists, keep, O=O, LSE=LSE)
 
-    def bwd():
-        B.attn_bwd(shp, Q, K, V, O, LSE, dO, lists, keep, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+    def bwd(stages=None):
+        B.attn_bwd(shp, Q, K, V, O, LSE, dO, lists, keep, dQ=dQ, dK=dK, dV=dV, workspace=ws, stages=stages)
 
     def step():
         indices()
@@ -156,6 +156,9 @@ def main():
         "prune": timed(torch, lambda: B.prune_q(shp, Q, wl.keep_ratio, keep), args.steps),
         "attn_fwd": timed(torch, fwd, args.steps),
         "attn_bwd": timed(torch, bwd, args.steps),
+        "bwd_pre": timed(torch, lambda: bwd(B.BWD_PRE), args.steps),
+        "bwd_dq": timed(torch, lambda: bwd(B.BWD_DQ), args.steps),
+        "bwd_dkv": timed(torch, lambda: bwd(B.BWD_DKV), args.steps),
     }
     nnz = int(lists.nnz.item())
     f = nnz / (shp.rows * shp.N)
@@ -163,8 +166,17 @@ def main():
     t_attn = parts["attn_fwd"] + parts["attn_bwd"]
     actual_tflops = 14 * pair_flops / (t_attn * 1e-3) / 1e12
     dense_flops = 14.0 * wl.B * wl.H * wl.L * wl.L * wl.d
-    fwd_tflops = 4 * pair_flops / (parts["attn_fwd"] * 1e-3) / 1e12
-    bwd_tflops = 10 * pair_flops / (parts["attn_bwd"] * 1e-3) / 1e12
+    # credited FLOPs per listed (query block, KV block) pair, in units of d*n_keep*Bk:
+    # forward 4 (QK^T, PV); dK/dV kernel 8 (S, dP, dV, dK); dQ kernel 2 (its S/dP recompute is not credited)
+    kernels = {"fwd_mfma_kernel": ("attn_fwd", 4), "bwd_dkv_mfma_kernel": ("bwd_dkv", 8), "bwd_dq_mfma_kernel": ("bwd_dq", 2)}
+    dominant = max(kernels, key=lambda k: parts[kernels[k][0]])
+
+    def roof(kname):
+        call, mult = kernels[kname]
+        tf = mult * pair_flops / (parts[call] * 1e-3) / 1e12
+        return {"kernel": kname, "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / PEAK_BF16_TFLOPS, "traffic": None, "avg_launch_ms": parts[call],
+                "algorithmic_flops_per_launch": mult * pair_flops}
 
     out = {
         "metric": "bsa_fwd_bwd_ms_per_layer", "value": ms_step, "unit": "ms", "n_gpus": 1,
@@ -177,10 +189,8 @@ def main():
         "effective_tflops": dense_flops / (ms_step * 1e-3) / 1e12,
         "actual_tflops": actual_tflops,
         "actual_pct_of_bf16_peak": 100.0 * actual_tflops / PEAK_BF16_TFLOPS,
-        "roofline": {"kernel": "attn_bwd (pre + dQ + dK/dV)", "bound": "mfma", "achieved": bwd_tflops,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": bwd_tflops / PEAK_BF16_TFLOPS, "traffic": None},
-        "roofline_fwd": {"kernel": "fwd_mfma_kernel", "bound": "mfma", "achieved": fwd_tflops, "peak": PEAK_BF16_TFLOPS,
-                         "unit": "TFLOP/s", "frac": fwd_tflops / PEAK_BF16_TFLOPS, "traffic": None},
+        "roofline": roof(dominant),
+        "roofline_other": [roof(k) for k in kernels if k != dominant],
         "wall_s_timed_region": wall,
     }
     pool_bytes = 2 * Q.numel() * Q.element_size() + 2 * Qbar.numel() * 8 + keep.numel() * 4 + Q.numel() * Q.element_size()

@@ -9,7 +9,8 @@
  * filled with their block center's output (Sec. 3.2.2, "Token Filling").
  *
  * Conventions shared by every entry point
- *   - All data pointers are DEVICE pointers on the current HIP device unless stated.
+ *   - All data pointers are DEVICE pointers on the current HIP device unless stated,
+ *     16-byte aligned (tensors, workspaces) or 4-byte aligned (index arrays).
  *   - Q, K, V, O, dO, dQ, dK, dV are contiguous [B, H, L, d] in RASTER token order
  *     n = t*Hs*Ws + h*Ws + w (Sec. 3.1), L = T*Hs*Ws; element type per shape.dtype.
  *   - Blocks: (Ct, Ch, Cw) must divide (T, Hs, Ws) (Sec. 3.2.1).  Bk = Ct*Ch*Cw tokens
@@ -39,7 +40,7 @@ enum bsa_status {
   BSA_OK = 0,
   BSA_ERR_NULL = -1,        /* a required pointer is NULL */
   BSA_ERR_SHAPE = -2,       /* non-positive extent, block does not divide grid, unsupported d / Bk / N */
-  BSA_ERR_RANGE = -3,       /* threshold or keep ratio outside (0, 1], n_keep outside [1, Bk] */
+  BSA_ERR_RANGE = -3,       /* threshold or keep ratio outside (0, 1], n_keep outside [1, Bk], sm_scale <= 0 */
   BSA_ERR_CAPACITY = -4,    /* index buffer smaller than the worst case rows*N */
   BSA_ERR_DTYPE = -5,       /* shape.dtype is neither BSA_F32 nor BSA_BF16 */
   BSA_ERR_LAUNCH = -6,      /* the HIP runtime reported a launch error */
@@ -131,6 +132,21 @@ int bsa_attn_bwd(const bsa_shape_t* shape, const void* Q, const void* K, const v
                  const int32_t* keep_idx, int n_keep, float sm_scale,
                  void* dQ, void* dK, void* dV,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same backward, restricted to a subset of its three kernels, so that a profiler or
+ * benchmark can time each one between its own pair of events: BSA_BWD_PRE gathers the
+ * retained rows and forms delta, BSA_BWD_DQ and BSA_BWD_DKV read what PRE left in the
+ * workspace.  bsa_attn_bwd() is stages = BSA_BWD_PRE | BSA_BWD_DQ | BSA_BWD_DKV, in that order.
+ */
+enum bsa_bwd_stage { BSA_BWD_PRE = 1, BSA_BWD_DQ = 2, BSA_BWD_DKV = 4 };
+int bsa_attn_bwd_stages(const bsa_shape_t* shape, const void* Q, const void* K, const void* V,
+                        const void* O, const float* LSE, const void* dO,
+                        const int32_t* q2k_ptr, const int32_t* q2k_idx,
+                        const int32_t* k2q_ptr, const int32_t* k2q_idx,
+                        const int32_t* keep_idx, int n_keep, float sm_scale,
+                        void* dQ, void* dK, void* dV,
+                        void* workspace, size_t workspace_bytes, unsigned stages, void* stream);
 
 /*
  * Full (dense) softmax attention of Eq. 1 at the same shape, forward and backward: the

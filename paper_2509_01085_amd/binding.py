@@ -20,7 +20,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbsa.so"
 F32, BF16 = 0, 1
 EXPORTS = (
     "bsa_strerror", "bsa_n_keep", "bsa_pool_blocks", "bsa_select_workspace_bytes", "bsa_select_kv",
-    "bsa_prune_q", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd",
+    "bsa_prune_q", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd", "bsa_attn_bwd_stages",
     "bsa_dense_bwd_workspace_bytes", "bsa_dense_attn_fwd", "bsa_dense_attn_bwd",
 )
 
@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
         L.bsa_bwd_workspace_bytes.restype, L.bsa_bwd_workspace_bytes.argtypes = sz, [P, i32]
         L.bsa_attn_bwd.restype = C.c_int
         L.bsa_attn_bwd.argtypes = [P] + [vp] * 11 + [i32, f32, vp, vp, vp, vp, sz, vp]
+        L.bsa_attn_bwd_stages.restype = C.c_int
+        L.bsa_attn_bwd_stages.argtypes = [P] + [vp] * 11 + [i32, f32, vp, vp, vp, vp, sz, C.c_uint, vp]
         L.bsa_dense_bwd_workspace_bytes.restype, L.bsa_dense_bwd_workspace_bytes.argtypes = sz, [P]
         L.bsa_dense_attn_fwd.restype = C.c_int
         L.bsa_dense_attn_fwd.argtypes = [P, vp, vp, vp, f32, vp, vp, vp]
@@ -200,8 +202,12 @@ def bwd_workspace_bytes(shape: Shape, n_keep_: int) -> int:
     return lib().bsa_bwd_workspace_bytes(C.byref(shape.c()), n_keep_)
 
 
+BWD_PRE, BWD_DQ, BWD_DKV = 1, 2, 4
+
+
 def attn_bwd(shape: Shape, Q, K, V, O, LSE, dO, lists: KvLists, keep_idx: torch.Tensor,
-             sm_scale: Optional[float] = None, dQ=None, dK=None, dV=None, workspace: Optional[torch.Tensor] = None):
+             sm_scale: Optional[float] = None, dQ=None, dK=None, dV=None, workspace: Optional[torch.Tensor] = None,
+             stages: Optional[int] = None):
     if sm_scale is None:
         sm_scale = 1.0 / sqrt(shape.d)
     nk = keep_idx.shape[-1]
@@ -210,10 +216,13 @@ def attn_bwd(shape: Shape, Q, K, V, O, LSE, dO, lists: KvLists, keep_idx: torch.
     dV = torch.empty_like(V) if dV is None else dV
     if workspace is None:
         workspace = torch.empty(max(1, bwd_workspace_bytes(shape, nk)), dtype=torch.uint8, device=Q.device)
-    st = lib().bsa_attn_bwd(C.byref(shape.c()), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO),
-                            _ptr(lists.q2k_ptr), _ptr(lists.q2k_idx), _ptr(lists.k2q_ptr), _ptr(lists.k2q_idx),
-                            _ptr(keep_idx), nk, sm_scale, _ptr(dQ), _ptr(dK), _ptr(dV),
-                            _ptr(workspace), workspace.numel(), _stream())
+    args = (C.byref(shape.c()), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO),
+            _ptr(lists.q2k_ptr), _ptr(lists.q2k_idx), _ptr(lists.k2q_ptr), _ptr(lists.k2q_idx),
+            _ptr(keep_idx), nk, sm_scale, _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), workspace.numel())
+    if stages is None:
+        st = lib().bsa_attn_bwd(*args, _stream())
+    else:
+        st = lib().bsa_attn_bwd_stages(*args, stages, _stream())
     _check(st, "bsa_attn_bwd")
     return dQ, dK, dV
 

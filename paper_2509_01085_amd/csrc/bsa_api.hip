@@ -51,7 +51,7 @@ const char* bsa_strerror(int status) {
     case BSA_OK: return "ok";
     case BSA_ERR_NULL: return "a required pointer is NULL";
     case BSA_ERR_SHAPE: return "unsupported shape (extents must be positive, the block must divide the grid, d%8==0, d<=256, Bk<=256, N<=8192)";
-    case BSA_ERR_RANGE: return "threshold / keep ratio must lie in (0,1] and n_keep in [1,Bk]";
+    case BSA_ERR_RANGE: return "threshold / keep ratio must lie in (0,1], n_keep in [1,Bk], sm_scale > 0, stages in 1..7";
     case BSA_ERR_CAPACITY: return "index buffer smaller than rows*N";
     case BSA_ERR_DTYPE: return "dtype must be BSA_F32 or BSA_BF16";
     case BSA_ERR_LAUNCH: return "HIP launch error";
@@ -116,7 +116,7 @@ int bsa_attn_fwd(const bsa_shape_t* shape, const void* Q, const void* K, const v
   int rc = make_geom(shape, &g);
   if (rc) return rc;
   if (!Q || !K || !V || !q2k_ptr || !q2k_idx || !keep_idx || !O || !LSE) return BSA_ERR_NULL;
-  if (n_keep < 1 || n_keep > g.Bk || !std::isfinite(sm_scale)) return BSA_ERR_RANGE;
+  if (n_keep < 1 || n_keep > g.Bk || !(sm_scale > 0.f) || !std::isfinite(sm_scale)) return BSA_ERR_RANGE;
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.q2k_ptr = q2k_ptr; a.q2k_idx = q2k_idx; a.keep_idx = keep_idx;
   a.n_keep = n_keep; a.sm_scale = sm_scale; a.O_out = O; a.LSE_out = LSE;
@@ -137,19 +137,32 @@ int bsa_attn_bwd(const bsa_shape_t* shape, const void* Q, const void* K, const v
                  const int32_t* q2k_idx, const int32_t* k2q_ptr, const int32_t* k2q_idx,
                  const int32_t* keep_idx, int n_keep, float sm_scale, void* dQ, void* dK, void* dV,
                  void* workspace, size_t workspace_bytes, void* stream) {
+  return bsa_attn_bwd_stages(shape, Q, K, V, O, LSE, dO, q2k_ptr, q2k_idx, k2q_ptr, k2q_idx, keep_idx,
+                             n_keep, sm_scale, dQ, dK, dV, workspace, workspace_bytes,
+                             BSA_BWD_PRE | BSA_BWD_DQ | BSA_BWD_DKV, stream);
+}
+
+int bsa_attn_bwd_stages(const bsa_shape_t* shape, const void* Q, const void* K, const void* V,
+                        const void* O, const float* LSE, const void* dO, const int32_t* q2k_ptr,
+                        const int32_t* q2k_idx, const int32_t* k2q_ptr, const int32_t* k2q_idx,
+                        const int32_t* keep_idx, int n_keep, float sm_scale, void* dQ, void* dK,
+                        void* dV, void* workspace, size_t workspace_bytes, unsigned stages,
+                        void* stream) {
   Geom g;
   int rc = make_geom(shape, &g);
   if (rc) return rc;
   if (!Q || !K || !V || !O || !LSE || !dO || !q2k_ptr || !q2k_idx || !k2q_ptr || !k2q_idx ||
       !keep_idx || !dQ || !dK || !dV)
     return BSA_ERR_NULL;
-  if (n_keep < 1 || n_keep > g.Bk || !std::isfinite(sm_scale)) return BSA_ERR_RANGE;
+  if (n_keep < 1 || n_keep > g.Bk || !(sm_scale > 0.f) || !std::isfinite(sm_scale)) return BSA_ERR_RANGE;
   if (!workspace || workspace_bytes < bsa_bwd_workspace_bytes(shape, n_keep)) return BSA_ERR_WORKSPACE;
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.LSE_in = LSE; a.dO = dO;
   a.q2k_ptr = q2k_ptr; a.q2k_idx = q2k_idx; a.k2q_ptr = k2q_ptr; a.k2q_idx = k2q_idx;
   a.keep_idx = keep_idx; a.n_keep = n_keep; a.sm_scale = sm_scale;
   a.dQ = dQ; a.dK = dK; a.dV = dV; a.ws = workspace;
+  if (stages == 0 || (stages & ~7u)) return BSA_ERR_RANGE;
+  a.stages = stages;
   if (mfma_supported(g, shape->dtype, n_keep)) return launch_bwd_mfma(g, a, (hipStream_t)stream);
   return launch_bwd_generic(g, shape->dtype, a, (hipStream_t)stream);
 }
@@ -175,7 +188,7 @@ int bsa_dense_attn_fwd(const bsa_shape_t* shape, const void* Q, const void* K, c
   int rc = dense_geom(shape, &g);
   if (rc) return rc;
   if (!Q || !K || !V || !O || !LSE) return BSA_ERR_NULL;
-  if (!std::isfinite(sm_scale)) return BSA_ERR_RANGE;
+  if (!(sm_scale > 0.f) || !std::isfinite(sm_scale)) return BSA_ERR_RANGE;
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.n_keep = g.Bk; a.sm_scale = sm_scale; a.O_out = O; a.LSE_out = LSE;
   if (mfma_supported(g, shape->dtype, g.Bk)) return launch_fwd_mfma(g, a, (hipStream_t)stream);
@@ -189,11 +202,12 @@ int bsa_dense_attn_bwd(const bsa_shape_t* shape, const void* Q, const void* K, c
   int rc = dense_geom(shape, &g);
   if (rc) return rc;
   if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV) return BSA_ERR_NULL;
-  if (!std::isfinite(sm_scale)) return BSA_ERR_RANGE;
+  if (!(sm_scale > 0.f) || !std::isfinite(sm_scale)) return BSA_ERR_RANGE;
   if (!workspace || workspace_bytes < bsa_dense_bwd_workspace_bytes(shape)) return BSA_ERR_WORKSPACE;
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.LSE_in = LSE; a.dO = dO; a.n_keep = g.Bk;
   a.sm_scale = sm_scale; a.dQ = dQ; a.dK = dK; a.dV = dV; a.ws = workspace;
+  a.stages = BSA_BWD_PRE | BSA_BWD_DQ | BSA_BWD_DKV;
   if (mfma_supported(g, shape->dtype, g.Bk)) return launch_bwd_mfma(g, a, (hipStream_t)stream);
   return launch_bwd_generic(g, shape->dtype, a, (hipStream_t)stream);
 }

@@ -397,12 +397,12 @@ static int fwd_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
 template <typename T>
 static int bwd_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
   GenericWs w = carve(g, a.n_keep, a.ws);
-  hipLaunchKernelGGL(bwd_pre_generic_kernel<T>, dim3(g.rows), dim3(256), 0, st, g, a, w);
+  if (a.stages & BSA_BWD_PRE) hipLaunchKernelGGL(bwd_pre_generic_kernel<T>, dim3(g.rows), dim3(256), 0, st, g, a, w);
   const size_t lds = (size_t)((2 * QT + 2 * KT) * (g.d + 1) + 2 * QT * (KT + 1)) * 4;
   if (int rc = set_lds(bwd_dq_generic_kernel<T>, lds)) return rc;
   if (int rc = set_lds(bwd_dkv_generic_kernel<T>, lds)) return rc;
-  hipLaunchKernelGGL(bwd_dq_generic_kernel<T>, dim3(g.rows, (a.n_keep + QT - 1) / QT), dim3(256), lds, st, g, a, w);
-  hipLaunchKernelGGL(bwd_dkv_generic_kernel<T>, dim3(g.rows, (g.Bk + KT - 1) / KT), dim3(256), lds, st, g, a, w);
+  if (a.stages & BSA_BWD_DQ) hipLaunchKernelGGL(bwd_dq_generic_kernel<T>, dim3(g.rows, (a.n_keep + QT - 1) / QT), dim3(256), lds, st, g, a, w);
+  if (a.stages & BSA_BWD_DKV) hipLaunchKernelGGL(bwd_dkv_generic_kernel<T>, dim3(g.rows, (g.Bk + KT - 1) / KT), dim3(256), lds, st, g, a, w);
   return check_launch();
 }
 

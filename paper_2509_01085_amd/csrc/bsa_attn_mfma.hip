@@ -809,7 +809,7 @@ template <int D, int NQT>
 static int launch_bwd_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
   using T = BwdTile<D, NQT>;
   const int W = (g.N + 31) / 32;
-  hipLaunchKernelGGL((bwd_pre_mfma_kernel<D, NQT>), dim3(g.rows), dim3(256), 0, st, g, a);
+  if (a.stages & BSA_BWD_PRE) hipLaunchKernelGGL((bwd_pre_mfma_kernel<D, NQT>), dim3(g.rows), dim3(256), 0, st, g, a);
   const size_t lds_q = (size_t)2 * (2 * BK * Stage<D>::KLD + D * VLD) * 2 + (size_t)G * W * 4;
   const size_t lds_kv = (size_t)2 * T::BYTES + (size_t)2 * W * 4;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_mfma_kernel<D, NQT>),
@@ -817,8 +817,8 @@ static int launch_bwd_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
       hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_mfma_kernel<D, NQT>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv) != hipSuccess)
     return BSA_ERR_LAUNCH;
-  hipLaunchKernelGGL((bwd_dq_mfma_kernel<D, NQT>), dim3((g.N + G - 1) / G, g.B * g.H), dim3(256), lds_q, st, g, a);
-  hipLaunchKernelGGL((bwd_dkv_mfma_kernel<D, NQT>), dim3((g.N + 1) / 2, g.B * g.H), dim3(256), lds_kv, st, g, a);
+  if (a.stages & BSA_BWD_DQ) hipLaunchKernelGGL((bwd_dq_mfma_kernel<D, NQT>), dim3((g.N + G - 1) / G, g.B * g.H), dim3(256), lds_q, st, g, a);
+  if (a.stages & BSA_BWD_DKV) hipLaunchKernelGGL((bwd_dkv_mfma_kernel<D, NQT>), dim3((g.N + 1) / 2, g.B * g.H), dim3(256), lds_kv, st, g, a);
   return check_launch();
 }
 

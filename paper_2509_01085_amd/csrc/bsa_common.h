@@ -81,6 +81,7 @@ struct AttnArgs {
   void *O_out, *dQ, *dK, *dV;
   float* LSE_out;
   void* ws;
+  unsigned stages;  // backward only: which of its kernels to launch (bsa_bwd_stage bits)
 };
 
 // plain-ALU fp32-accumulate kernels: any supported shape, fp32 or bf16 storage

@@ -18,6 +18,22 @@ from paper_2509_01085_amd import binding as B
 SELECT_MARGIN = 1e-10
 
 
+def progress(msg: str) -> None:
+    """Progress line of a long test: stdout (visible with -s) and a file under gpurun_out/,
+    so that a run whose output pytest captures is still seen to be alive."""
+    import os
+    import time
+
+    print(msg, flush=True)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    try:
+        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(root, "gpurun_out", "test_progress.log"), "a") as f:
+            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+    except OSError:
+        pass
+
+
 def shape_of(wl: Workload) -> B.Shape:
     return B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16)
 
@@ -158,3 +174,24 @@ def tol_of(wl: Workload) -> float:
 
 def host_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float64).cpu().numpy()
+
+
+def rounding_bounds_kv_block(xi: dict, part: o.Partition, ix, sm_scale: float, j: int):
+    """E_dK, E_dV of rounding_bounds() for the Bk tokens of KV block j alone."""
+    u = BF16_U
+    tok = part.block_tokens()
+    X = {k: np.asarray(v, dtype=np.float64) for k, v in xi.items()}
+    kj, vj = X["K"][tok[j]], X["V"][tok[j]]
+    EK, EV = np.zeros_like(kj), np.zeros_like(vj)
+    for i in ix.k2q_idx[ix.k2q_ptr[j]:ix.k2q_ptr[j + 1]]:
+        rows = tok[i, ix.keep_idx[i]]
+        keys = tok[ix.q2k_idx[ix.q2k_ptr[i]:ix.q2k_ptr[i + 1]]].reshape(-1)
+        q = X["Q"][rows]
+        out, lse, _ = o.attend_block(q, X["K"][keys], X["V"][keys], sm_scale)
+        g = o.folded_grad(X["dO"], part, ix.keep_idx, int(i), tok)
+        Pj = np.exp((q @ kj.T) * sm_scale - lse[:, None])
+        dSj = Pj * (g @ vj.T - (g * out).sum(axis=1, keepdims=True))
+        ddS = u * (Pj * (np.abs(g) @ np.abs(vj).T) + np.abs(dSj))
+        EK += sm_scale * (ddS.T @ np.abs(q))
+        EV += 2 * u * (Pj.T @ np.abs(g))
+    return EK, EV

@@ -1,0 +1,103 @@
+"""GPU parity at the full sizes of the named workloads, in the launch configuration the
+benchmark times.  Index work is compared bit for bit on whole heads; attention outputs and
+gradients on sampled query blocks (O, LSE, dQ) and sampled KV blocks (dK, dV), which the
+oracle computes one by one in fp64.  Heads that are not sampled hold zeros on the device
+(they still run through every kernel)."""
+from math import sqrt
+
+import numpy as np
+import pytest
+import torch
+
+from bsa_workloads import WORKLOADS, head_inputs
+from oracle import bsa_oracle as o
+from paper_2509_01085_amd import binding as B
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+# workload -> (heads checked, query blocks sampled per head, KV blocks sampled per head)
+PLAN = {
+    "wan1p3b": ((0, 7, 11), 6, 2),
+    "hd720p": ((3, 39), 4, 1),
+    "long": ((5,), 4, 1),
+}
+
+
+MAX_LISTERS = 600
+
+
+def _sample(rng, n, k, always=()):
+    picks = set(always)
+    while len(picks) < min(n, k + len(always)):
+        picks.add(int(rng.integers(0, n)))
+    return sorted(picks)
+
+
+@pytest.mark.parametrize("name", list(PLAN))
+def test_full_size_parity(name):
+    wl = WORKLOADS[name]
+    heads, n_qb, n_kb = PLAN[name]
+    part = U.part_of(wl)
+    tok = part.block_tokens()
+    scale = 1 / sqrt(wl.d)
+    U.progress(f"[{name}] generating heads {heads}")
+    x = U.device_inputs(wl, heads=heads)
+    shp, Qbar, Kbar, lists, keep = U.run_indices(wl, x)
+    O, LSE = B.attn_fwd(shp, x["Q"], x["K"], x["V"], lists, keep)
+    dQ, dK, dV = B.attn_bwd(shp, x["Q"], x["K"], x["V"], O, LSE, x["dO"], lists, keep)
+    torch.cuda.synchronize()
+    host = U.lists_to_host(shp, lists)
+    U.progress(f"[{name}] GPU done, nnz={host['nnz']} f={host['nnz'] / (shp.rows * shp.N):.3f}")
+    rng = np.random.default_rng(123)
+    worst = {}
+    for h in heads:
+        xi = head_inputs(wl, 0, h)
+        ix = o.bsa_indices(xi["Q"], xi["K"], part, wl.threshold, wl.keep_ratio)
+        # ---- index work: whole head, bit for bit
+        assert np.array_equal(Qbar[0, h].cpu().numpy(), ix.Qbar) and np.array_equal(Kbar[0, h].cpu().numpy(), ix.Kbar)
+        assert np.array_equal(keep[0, h].cpu().numpy(), ix.keep_idx)
+        scores = o.block_scores(ix.Qbar, ix.Kbar, scale) if ix.select_margin <= U.SELECT_MARGIN else None
+        differing = U.check_lists_against_oracle(wl, shp, host, 0, h, ix, scores)
+        U.progress(f"[{name}] head {h}: lists ok (margin {ix.select_margin:.2e}, rows within rounding reach: {differing})")
+        if differing:
+            continue  # attention below assumes identical lists
+        # ---- forward and dQ on sampled query blocks (always include the longest list)
+        lens = np.diff(ix.q2k_ptr)
+        qb = _sample(rng, part.N, n_qb, always=(int(np.argmax(lens)), int(np.argmin(lens))))
+        rO, rL = o.attn_fwd(xi["Q"], xi["K"], xi["V"], part, ix.q2k_ptr, ix.q2k_idx, ix.keep_idx, scale, q_blocks=qb)
+        O_in = U.o_storage_of(wl)(rO)
+        rdQ, _, _ = o.attn_bwd(xi["Q"], xi["K"], xi["V"], xi["dO"], part, ix.q2k_ptr, ix.q2k_idx, ix.keep_idx, scale,
+                               q_blocks=qb, O_in=O_in)
+        E = U.rounding_bounds(xi, part, ix, scale, q_blocks=qb)
+        sel = tok[qb].reshape(-1)
+        gO, gL, gdQ = (U.host_f64(t[0, h])[sel] for t in (O, LSE, dQ))
+        # RMS over the sampled rows stands in for the tensor's RMS
+        figs = {"O": U.parity_excess(gO, rO[sel], wl.dtype, E["O"][sel]),
+                "dQ": U.parity_excess(gdQ, rdQ[sel], wl.dtype, E["dQ"][sel]),
+                "LSE": float(np.abs(gL - rL[sel]).max())}
+        # ---- dK, dV on sampled KV blocks.  One KV block costs one oracle forward per listing
+        # query block, so the sample takes the shortest lists and skips lists beyond MAX_LISTERS.
+        klens = np.diff(ix.k2q_ptr)
+        order = [int(j) for j in np.argsort(klens, kind="stable") if klens[j] > 0]
+        for j in order[:n_kb]:
+            if klens[j] > MAX_LISTERS:
+                U.progress(f"[{name}] head {h}: KV block {j} has {klens[j]} listers (> {MAX_LISTERS}): dK/dV not sampled here")
+                continue
+            # the stored O the backward reads, for every query block that lists j
+            need = [int(i) for i in ix.k2q_idx[ix.k2q_ptr[j]:ix.k2q_ptr[j + 1]]]
+            fO, _ = o.attn_fwd(xi["Q"], xi["K"], xi["V"], part, ix.q2k_ptr, ix.q2k_idx, ix.keep_idx, scale, q_blocks=need)
+            rdK, rdV = o.attn_bwd_kv_block(xi["Q"], xi["K"], xi["V"], xi["dO"], part, ix.q2k_ptr, ix.q2k_idx,
+                                           ix.k2q_ptr, ix.k2q_idx, ix.keep_idx, scale, j, O_in=U.o_storage_of(wl)(fO))
+            EK, EV = U.rounding_bounds_kv_block(xi, part, ix, scale, j)
+            gdK, gdV = U.host_f64(dK[0, h])[tok[j]], U.host_f64(dV[0, h])[tok[j]]
+            figs["dK"] = max(figs.get("dK", 0.0), U.parity_excess(gdK, rdK, wl.dtype, EK))
+            figs["dV"] = max(figs.get("dV", 0.0), U.parity_excess(gdV, rdV, wl.dtype, EV))
+        U.progress(f"[{name}] head {h}: blocks {qb}: {figs}")
+        for k, v in figs.items():
+            worst[k] = max(worst.get(k, 0.0), v)
+    tol = U.tol_of(wl)
+    assert worst, "no head could be compared"
+    for k, v in worst.items():
+        assert v < tol, (k, v)
