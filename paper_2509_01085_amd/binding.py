@@ -15,7 +15,8 @@ from typing import Optional
 
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbsa.so")
+# BSA_LIB selects another build of the same library (e.g. one compiled with different tuning flags)
+_LIB_PATH = os.environ.get("BSA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbsa.so")
 
 F32, BF16 = 0, 1
 EXPORTS = (

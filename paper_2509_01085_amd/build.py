@@ -34,31 +34,43 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
-    if r.returncode:
-        raise RuntimeError(f"hipcc failed for {src}:\n{err}")
-    if err.strip():
-        print(err, file=sys.stderr)
-    return obj
+def build(verbose: bool = True, out: str = LIB, extra_flags=()) -> str:
+    """Compile every source and link `out`.  `extra_flags` (e.g. -DNAME=value tuning macros)
+    go to every compile; objects of such variant builds live in their own folder."""
+    global OBJ
+    obj_dir = OBJ if out == LIB else OBJ + "_" + os.path.basename(out).replace(".", "_")
+    os.makedirs(obj_dir, exist_ok=True)
 
+    def comp(src):
+        obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
+        cmd = [hipcc(), *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        noise = "is not a recognized feature for this target"
+        err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
+        if r.returncode:
+            raise RuntimeError(f"hipcc failed for {src}:\n{err}")
+        if err.strip():
+            print(err, file=sys.stderr)
+        return obj
 
-def build(verbose: bool = True) -> str:
-    os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+        objs = list(ex.map(comp, SOURCES))
+    LIB_OUT = out
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_OUT, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode:
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", LIB_OUT)
+    return LIB_OUT
 
 
 if __name__ == "__main__":
-    build()
+    # python -m paper_2509_01085_amd.build [-o other.so] [-DFLAG ...]
+    argv = sys.argv[1:]
+    out = LIB
+    if "-o" in argv:
+        k = argv.index("-o")
+        out = os.path.abspath(argv[k + 1])
+        del argv[k:k + 2]
+    build(out=out, extra_flags=tuple(argv))

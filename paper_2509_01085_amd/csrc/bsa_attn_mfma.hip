@@ -69,6 +69,17 @@ struct Stage {
   }
 };
 
+// Workgroups are dispatched round-robin over the 8 XCDs (id n runs on XCD n % 8), each with its
+// own L2.  Remap the linear id so that every XCD works through one contiguous range of
+// (head, group) units in order: workgroups that run side by side on an XCD then belong to the
+// same head and walk the same K/V tiles in step, which is what lets that L2 serve the re-reads.
+__device__ inline int xcd_remap(int n, int total) {
+  const int q = total >> 3, r = total & 7, x = n & 7;
+  return x * q + min(x, r) + (n >> 3);
+}
+
+#define BSA_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 // Ascending walk over the union of the workgroup's KV lists, kept as bit masks in LDS.
 struct UnionWalk {
   const uint32_t* masks;  // [G][W]
@@ -105,8 +116,10 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void fwd_mfma_kernel(Geom 
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = lane >> 5, col = lane & 31;
-  const int64_t bh = blockIdx.y;
-  const int i = blockIdx.x * G + wave;  // this wavefront's query block
+  const int ngroups = (g.N + G - 1) / G;
+  const int unit = xcd_remap(blockIdx.x, gridDim.x);
+  const int64_t bh = unit / ngroups;
+  const int i = (unit % ngroups) * G + wave;  // this wavefront's query block
   const bool valid = i < g.N;
   const int64_t row = bh * g.N + i;
   const int W = (g.N + 31) / 32;
@@ -155,6 +168,10 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void fwd_mfma_kernel(Geom 
       qf[qt][s] = as_frag(v);
     }
   }
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+    for (int s = 0; s < DS; ++s) settle(qf[qt][s]);
   __syncthreads();
 
   f32x16 o[NQT][DT];
@@ -182,10 +199,28 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void fwd_mfma_kernel(Geom 
   int buf = 0;
   while (jb >= 0) {
     const int jn = walk.next(mine_next);
+#ifndef BSA_EXP_NOLOAD
     if (jn >= 0) st.load(g, Kh, Vh, jn, koff);
+#endif
+#ifdef BSA_EXP_NOCOMPUTE
+    mine = false;
+#endif
     if (mine) {
-      const uint16_t* Kb = Ks + buf * BK * KLD;
-      const uint16_t* Vb = Vs + buf * D * VLD;
+      // The 4*DS A fragments of a tile (K rows for both key halves, then V^T) are read from
+      // LDS through a ring of RING registers-fragments, RING MFMAs ahead of their use, so the
+      // read latency overlaps matrix work instead of preceding every single MFMA.
+      constexpr int RING = 8, NF = 4 * DS;
+      const uint16_t* kp = Ks + buf * BK * KLD + col * KLD + 8 * grp;
+      const uint16_t* vp = Vs + buf * D * VLD + col * VLD + 8 * grp;
+      auto frag = [&](int f) -> bf16x8 {
+        if (f < 2 * DS) return lds_frag(kp + (32 * (f / DS)) * KLD + 16 * (f % DS));
+        const int v = f - 2 * DS;
+        return lds_frag(vp + (32 * (v / 4)) * VLD + 16 * (v % 4));
+      };
+      bf16x8 ring[RING];
+#pragma unroll
+      for (int f = 0; f < RING; ++f) ring[f] = frag(f);
+      BSA_SCHED_FENCE();
       f32x16 s[NQT][2];
 #pragma unroll
       for (int qt = 0; qt < NQT; ++qt)
@@ -194,13 +229,12 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void fwd_mfma_kernel(Geom 
 #pragma unroll
           for (int r = 0; r < 16; ++r) s[qt][kt][r] = 0.f;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int f = 0; f < 2 * DS; ++f) {
 #pragma unroll
-        for (int sp = 0; sp < DS; ++sp) {
-          const bf16x8 kfrag = lds_frag(Kb + (32 * kt + col) * KLD + 16 * sp + 8 * grp);
-#pragma unroll
-          for (int qt = 0; qt < NQT; ++qt) s[qt][kt] = mfma32(kfrag, qf[qt][sp], s[qt][kt]);
-        }
+        for (int qt = 0; qt < NQT; ++qt) s[qt][f / DS] = mfma32(ring[f % RING], qf[qt][f % DS], s[qt][f / DS]);
+        if (f + RING < NF) ring[f % RING] = frag(f + RING);
+        if (f & 1) BSA_SCHED_FENCE();
+      }
       bf16x8 pf[NQT][4];
 #pragma unroll
       for (int qt = 0; qt < NQT; ++qt) {
@@ -208,41 +242,43 @@ __global__ __launch_bounds__(256, (NQT == 1 ? 2 : 1)) void fwd_mfma_kernel(Geom 
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            s[qt][kt][r] *= c2;
-            mx = fmaxf(mx, s[qt][kt][r]);
-          }
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[qt][kt][r]);
         mx = fmaxf(mx, xor32(mx));
-        const float mnew = fmaxf(m[qt], mx);
+        const float mnew = fmaxf(m[qt], mx * c2);  // c2 > 0: the maximum commutes with the scaling
         const float alpha = __builtin_amdgcn_exp2f(m[qt] - mnew);
         float sum = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(s[qt][kt][r] - mnew);
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qt][kt][r], c2, -mnew));
             s[qt][kt][r] = p;
             sum += p;
           }
         l[qt] = l[qt] * alpha + sum;  // per-lane partial; the lane pair is summed at the end
         m[qt] = mnew;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {  // rescale only when some row's maximum moved
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+          for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) o[qt][dt][r] *= alpha;
+            for (int r = 0; r < 16; ++r) o[qt][dt][r] *= alpha;
+        }
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) pf[qt][ks] = d_to_b(s[qt][ks >> 1], ks & 1);
       }
+      BSA_SCHED_FENCE();
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+      for (int f = 2 * DS; f < NF; ++f) {
+        const int v = f - 2 * DS;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const bf16x8 vfrag = lds_frag(Vb + (32 * dt + col) * VLD + 16 * ks + 8 * grp);
-#pragma unroll
-          for (int qt = 0; qt < NQT; ++qt) o[qt][dt] = mfma32(vfrag, pf[qt][ks], o[qt][dt]);
-        }
+        for (int qt = 0; qt < NQT; ++qt) o[qt][v / 4] = mfma32(ring[f % RING], pf[qt][v % 4], o[qt][v / 4]);
+        if (f + RING < NF) ring[f % RING] = frag(f + RING);
+        if (f & 1) BSA_SCHED_FENCE();
+      }
     }
+#ifndef BSA_EXP_NOLOAD
     if (jn >= 0) st.store(Ks + (buf ^ 1) * BK * KLD, Vs + (buf ^ 1) * D * VLD);
+#endif
     __syncthreads();
     buf ^= 1;
     jb = jn;
@@ -295,7 +331,7 @@ static int launch_fwd_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_mfma_kernel<D, NQT>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
     return BSA_ERR_LAUNCH;
-  hipLaunchKernelGGL((fwd_mfma_kernel<D, NQT>), dim3((g.N + G - 1) / G, g.B * g.H), dim3(256), lds, st, g, a);
+  hipLaunchKernelGGL((fwd_mfma_kernel<D, NQT>), dim3(((g.N + G - 1) / G) * g.B * g.H), dim3(256), lds, st, g, a);
   return check_launch();
 }
 
@@ -510,6 +546,16 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(Geom g, AttnArgs a) {
       gf[qt][s] = as_frag(gv);
     }
   }
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) {
+    settle(lse2[qt]);
+    settle(delta[qt]);
+#pragma unroll
+    for (int s = 0; s < DS; ++s) {
+      settle(qf[qt][s]);
+      settle(gf[qt][s]);
+    }
+  }
   __syncthreads();
 
   f32x16 dq[NQT][DT];
@@ -703,6 +749,11 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(Geom g, AttnArgs a) {
     }
     kf[s] = as_frag(kv);
     vf[s] = as_frag(vv);
+  }
+#pragma unroll
+  for (int s = 0; s < DS; ++s) {
+    settle(kf[s]);
+    settle(vf[s]);
   }
   f32x16 dk[DT], dv[DT];
 #pragma unroll

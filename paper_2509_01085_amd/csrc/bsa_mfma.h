@@ -58,6 +58,15 @@ __device__ inline bf16x8 d_to_b(const f32x16& d, int h) {
   return as_frag(v);
 }
 
+// Make the compiler treat x as consumed here, so that the wait for the (global) loads that
+// produce it is placed at this point.  Used on loop-invariant operands before a pipelined
+// loop: otherwise their first use inside the loop forces a wait for ALL outstanding loads,
+// including the prefetch issued a moment earlier, which serialises the pipeline.
+template <typename T>
+__device__ inline void settle(T& x) {
+  asm volatile("" : "+v"(x));
+}
+
 __device__ inline float xor32(float v) { return __shfl_xor(v, 32); }
 
 // Transpose a 4 (rows) x 8 (columns) block of bf16 held as four 16-byte rows; out[c] packs
