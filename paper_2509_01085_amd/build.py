@@ -17,13 +17,14 @@ SOURCES = [
     "bsa_select.hip",
     "bsa_attn_generic.hip",
     "bsa_attn_mfma.hip",
+    "bsa_attn_pipe.hip",
 ]
 # -ffp-contract=off: the decision kernels fix every rounding; packed-fp32 ops are disabled
 # on the test machines (some forms have produced wrong results).
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wall", "-Wno-unused-function",
+    "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
 ]
 
 

@@ -29,6 +29,8 @@ int make_geom(const bsa_shape_t* s, Geom* g) {
   g->Bk = (int)Bk; g->N = (int)N; g->L = (int)L; g->rows = (int)rows;
   g->center = (s->Ct / 2) * s->Ch * s->Cw + (s->Ch / 2) * s->Cw + (s->Cw / 2);
   g->dense = 0;
+  g->inv_Nw = g->Nw == 1 ? 0u : (uint32_t)(0x100000000ull / (uint32_t)g->Nw) + 1u;
+  g->inv_NwNh = g->Nw * g->Nh == 1 ? 0u : (uint32_t)(0x100000000ull / (uint32_t)(g->Nw * g->Nh)) + 1u;
   return BSA_OK;
 }
 
@@ -120,7 +122,7 @@ int bsa_attn_fwd(const bsa_shape_t* shape, const void* Q, const void* K, const v
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.q2k_ptr = q2k_ptr; a.q2k_idx = q2k_idx; a.keep_idx = keep_idx;
   a.n_keep = n_keep; a.sm_scale = sm_scale; a.O_out = O; a.LSE_out = LSE;
-  if (mfma_supported(g, shape->dtype, n_keep)) return launch_fwd_mfma(g, a, (hipStream_t)stream);
+  if (mfma_supported(g, shape->dtype, n_keep)) return launch_fwd_pipe(g, a, (hipStream_t)stream);
   return launch_fwd_generic(g, shape->dtype, a, (hipStream_t)stream);
 }
 
@@ -191,7 +193,7 @@ int bsa_dense_attn_fwd(const bsa_shape_t* shape, const void* Q, const void* K, c
   if (!(sm_scale > 0.f) || !std::isfinite(sm_scale)) return BSA_ERR_RANGE;
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.n_keep = g.Bk; a.sm_scale = sm_scale; a.O_out = O; a.LSE_out = LSE;
-  if (mfma_supported(g, shape->dtype, g.Bk)) return launch_fwd_mfma(g, a, (hipStream_t)stream);
+  if (mfma_supported(g, shape->dtype, g.Bk)) return launch_fwd_pipe(g, a, (hipStream_t)stream);
   return launch_fwd_generic(g, shape->dtype, a, (hipStream_t)stream);
 }
 

@@ -18,6 +18,7 @@ struct Geom {
   int rows;        // B*H*N
   int center;      // intra-block id of the critical token (Sec. 3.2.2)
   int dense;       // 1: tiles are runs of Bk consecutive raster tokens (dense baseline)
+  uint32_t inv_Nw, inv_NwNh;  // floor(2^32 / x) + 1 (0 when x == 1): n / x == umulhi(n, inv) for n < 2^16
 };
 
 // Raster index (Sec. 3.1) of intra-block token c of block i (Sec. 3.2.1).
@@ -32,6 +33,16 @@ __host__ __device__ inline int token_of(const Geom& g, int i, int c) {
 __host__ __device__ inline int block_origin(const Geom& g, int i) {
   if (g.dense) return i * g.Bk;
   const int bw = i % g.Nw, bh = (i / g.Nw) % g.Nh, bt = i / (g.Nw * g.Nh);
+  return ((bt * g.Ct) * g.Hs + bh * g.Ch) * g.Ws + bw * g.Cw;
+}
+
+// Same, division-free (block ids are < 2^16): for per-tile use inside pipelined loops.
+__device__ inline int block_origin_fast(const Geom& g, int i) {
+  if (g.dense) return i * g.Bk;
+  const int bt = g.inv_NwNh ? (int)__umulhi((uint32_t)i, g.inv_NwNh) : i;
+  const int rem = i - bt * g.Nw * g.Nh;
+  const int bh = g.inv_Nw ? (int)__umulhi((uint32_t)rem, g.inv_Nw) : rem;
+  const int bw = rem - bh * g.Nw;
   return ((bt * g.Ct) * g.Hs + bh * g.Ch) * g.Ws + bw * g.Cw;
 }
 
@@ -94,5 +105,6 @@ bool mfma_supported(const Geom& g, int dtype, int n_keep);
 int launch_fwd_mfma(const Geom& g, const AttnArgs& a, hipStream_t st);
 int launch_bwd_mfma(const Geom& g, const AttnArgs& a, hipStream_t st);
 size_t bwd_workspace_mfma(const Geom& g, int n_keep);
+int launch_fwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st);  // DMA-ring forward, same shapes
 
 }  // namespace bsa

@@ -67,6 +67,61 @@ __device__ inline void settle(T& x) {
   asm volatile("" : "+v"(x));
 }
 
+// ---- LDS tile format of the pipelined kernels -------------------------------------------
+// A tile is 64 rows of D bf16, rows unpadded (D*2 bytes).  The 16-byte chunk c of row r is
+// stored at chunk position c ^ swz<D>(r).  The LDS of gfx950 has 64 four-byte banks (256
+// bytes per cycle); the swizzle makes both access patterns below conflict free:
+//   * row fragments (A operand with the tile row on the MFMA row index): ds_read_b128, a
+//     pass of 16 lanes reads the same chunk of 16 consecutive rows -> swz must be a bijection
+//     on r mod 16 (d = 128: a row is one 256-byte line) or on (r / 2) mod 8 (d = 64: two rows
+//     per line);
+//   * transposed fragments (A operand with the CHANNEL on the MFMA row index and 8 tile
+//     rows as contraction slots): two ds_read_b64_tr_b16, a pass of 32 lanes reads 4 aligned
+//     chunks of 4 consecutive rows -> those rows must differ in bits [3:2] of swz.
+// Tiles arrive by global->LDS DMA (global_load_lds_dwordx4: lane i's 16 bytes land at LDS
+// base + 16*i), so the swizzle is applied on the global side: the lane that fills LDS slot
+// (r, p) fetches chunk p ^ swz<D>(r) of row r.
+template <int D>
+__host__ __device__ constexpr int swz(int r) {
+  return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3)) : ((((r >> 1) & 1) << 2) | ((r >> 2) & 3));
+}
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes per lane, global -> LDS, no registers; completion is counted by vmcnt.
+// Issued as inline assembly on purpose: when the compiler knows of a pending LDS DMA it
+// waits for vmcnt(0) before every barrier and every LDS read it cannot disambiguate, which
+// would drain the whole prefetch ring each step.  The kernels order DMA against LDS reads
+// themselves: "s_waitcnt vmcnt(n)" for the tile about to be read, then a barrier.
+__device__ inline void dma16(const void* gsrc, void* lds_wave_base) {
+  // the LDS base travels in M0, a scalar register: make its wave-uniformity explicit
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)lds_wave_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gsrc), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+// Barrier without the memory fence of __syncthreads() (see dma16): callers pair it with
+// explicit waits.  The empty asm statements stop the compiler moving LDS accesses across it.
+__device__ inline void raw_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// A fragment from two transposed reads (contraction slots 0..3 and 4..7).
+__device__ inline bf16x8 lds_frag_tr(const uint8_t* p0, const uint8_t* p1) {
+  typedef __attribute__((address_space(3))) s16x4* lp;
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p0);
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p1);
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  const s16x8 v = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 __device__ inline float xor32(float v) { return __shfl_xor(v, 32); }
 
 // Transpose a 4 (rows) x 8 (columns) block of bf16 held as four 16-byte rows; out[c] packs
