@@ -130,7 +130,7 @@ size_t bsa_bwd_workspace_bytes(const bsa_shape_t* shape, int n_keep) {
   Geom g;
   if (make_geom(shape, &g)) return 0;
   if (n_keep < 1 || n_keep > g.Bk) return 0;
-  if (mfma_supported(g, shape->dtype, n_keep)) return bwd_workspace_mfma(g, n_keep);
+  if (mfma_supported(g, shape->dtype, n_keep)) return bwd_workspace_pipe(g, n_keep);
   return bwd_workspace_generic(g, n_keep);
 }
 
@@ -165,7 +165,7 @@ int bsa_attn_bwd_stages(const bsa_shape_t* shape, const void* Q, const void* K, 
   a.dQ = dQ; a.dK = dK; a.dV = dV; a.ws = workspace;
   if (stages == 0 || (stages & ~7u)) return BSA_ERR_RANGE;
   a.stages = stages;
-  if (mfma_supported(g, shape->dtype, n_keep)) return launch_bwd_mfma(g, a, (hipStream_t)stream);
+  if (mfma_supported(g, shape->dtype, n_keep)) return launch_bwd_pipe(g, a, (hipStream_t)stream);
   return launch_bwd_generic(g, shape->dtype, a, (hipStream_t)stream);
 }
 
@@ -180,7 +180,7 @@ static int dense_geom(const bsa_shape_t* shape, Geom* g) {
 size_t bsa_dense_bwd_workspace_bytes(const bsa_shape_t* shape) {
   Geom g;
   if (dense_geom(shape, &g)) return 0;
-  if (mfma_supported(g, shape->dtype, g.Bk)) return bwd_workspace_mfma(g, g.Bk);
+  if (mfma_supported(g, shape->dtype, g.Bk)) return bwd_workspace_pipe(g, g.Bk);
   return bwd_workspace_generic(g, g.Bk);
 }
 
@@ -210,7 +210,7 @@ int bsa_dense_attn_bwd(const bsa_shape_t* shape, const void* Q, const void* K, c
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.LSE_in = LSE; a.dO = dO; a.n_keep = g.Bk;
   a.sm_scale = sm_scale; a.dQ = dQ; a.dK = dK; a.dV = dV; a.ws = workspace;
   a.stages = BSA_BWD_PRE | BSA_BWD_DQ | BSA_BWD_DKV;
-  if (mfma_supported(g, shape->dtype, g.Bk)) return launch_bwd_mfma(g, a, (hipStream_t)stream);
+  if (mfma_supported(g, shape->dtype, g.Bk)) return launch_bwd_pipe(g, a, (hipStream_t)stream);
   return launch_bwd_generic(g, shape->dtype, a, (hipStream_t)stream);
 }
 

@@ -312,6 +312,602 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
   }
 }
 
+// =====================================================================================
+// Backward, same streaming scheme.  Three kernels, no floating-point atomics:
+//   pre   per query block: retained Q rows and the folded upstream gradient g (dO of the
+//         row; for the center row plus the dO of every pruned token, the gradient of the
+//         fill copy) as bf16 tiles in the swizzled LDS format, delta = <g, O> and LSE in the
+//         exp2 domain: one contiguous record per query block in the workspace.
+//   dQ    the forward's walk (four query blocks per workgroup, union of their KV lists):
+//         S^T = K Q^T, dP^T = V G^T, dS^T = P^T (dP^T - delta), dQ^T += K^T dS^T, one key half
+//         at a time; K^T comes from the same K tile through transposed LDS reads.
+//   dKV   a workgroup owns two adjacent KV blocks (a wavefront 32 keys, with its K^T / V^T
+//         fragments resident in registers) and walks the union of their k2q lists; the
+//         query-block records stream through a deep LDS ring by DMA:
+//         S = Qc K^T, dP = Gc V^T, dV^T += Gc^T P, dK^T += Qc^T dS.
+// =====================================================================================
+
+template <int D, int NQT>
+struct BwdRec {  // byte layout of one query block's record (workspace image == LDS image)
+  static constexpr int NQ = 32 * NQT;
+  static constexpr int RB = D * 2;
+  static constexpr int QC = 0;                  // [NQ][D] bf16, swizzled rows
+  static constexpr int GC = NQ * RB;            // [NQ][D] bf16, swizzled rows
+  static constexpr int LS = 2 * NQ * RB;        // float lse2[NQ]
+  static constexpr int DL = LS + NQ * 4;        // float delta[NQ]
+  static constexpr int BYTES = DL + NQ * 4;     // multiple of 256
+  static constexpr int CHUNKS = BYTES / 16;
+};
+
+template <int D, int NQT>
+__global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
+  using R = BwdRec<D, NQT>;
+  __shared__ float dpart[R::NQ][4];
+  __shared__ int keepflag[PBK];
+  __shared__ int qtok[R::NQ];
+  __shared__ int koff[PBK];
+  const int tid = threadIdx.x;
+  const int64_t row = blockIdx.x;
+  const int64_t bh = row / g.N;
+  const int i = row % g.N;
+  const uint16_t* Qh = static_cast<const uint16_t*>(a.Q) + bh * g.L * D;
+  const uint16_t* Oh = static_cast<const uint16_t*>(a.O) + bh * g.L * D;
+  const uint16_t* dOh = static_cast<const uint16_t*>(a.dO) + bh * g.L * D;
+  const float* Lh = a.LSE_in + bh * g.L;
+  uint8_t* rec = static_cast<uint8_t*>(a.ws) + row * (int64_t)R::BYTES;
+  const int origin = block_origin(g, i);
+
+  if (tid < PBK) {
+    koff[tid] = intra_offset(g, tid);
+    keepflag[tid] = 0;
+  }
+  __syncthreads();
+  if (tid < R::NQ) {
+    int c = -1;
+    if (tid < a.n_keep) c = g.dense ? tid : min(max(a.keep_idx[row * a.n_keep + tid], 0), PBK - 1);
+    qtok[tid] = c >= 0 ? origin + koff[c] : -1;
+    if (c >= 0) keepflag[c] = 1;
+  }
+  __syncthreads();
+  int cpos = -1;  // position of the center among the retained rows (same in every thread)
+  if (!g.dense)
+    for (int q = 0; q < a.n_keep; ++q)
+      if (qtok[q] == origin + koff[g.center]) cpos = q;
+
+  // thread (q = tid / 4 + 64 * pass, part = tid % 4) handles D/4 channels of row q
+  constexpr int CH = D / 4;
+  for (int q = tid >> 2; q < R::NQ; q += 64) {
+    const int part = tid & 3;
+    const int tok = qtok[q];
+    float dsum = 0.f;
+    for (int c8 = 0; c8 < CH; c8 += 8) {
+      const int ch = part * CH + c8;
+      u32x4 qv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
+      if (tok >= 0) {
+        qv = *reinterpret_cast<const u32x4*>(Qh + (int64_t)tok * D + ch);
+        gv = *reinterpret_cast<const u32x4*>(dOh + (int64_t)tok * D + ch);
+        const u32x4 ov = *reinterpret_cast<const u32x4*>(Oh + (int64_t)tok * D + ch);
+        float gf[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          gf[2 * e] = __uint_as_float(gv[e] << 16);
+          gf[2 * e + 1] = __uint_as_float(gv[e] & 0xffff0000u);
+        }
+        if (q == cpos) {  // fold the fill copies: pruned tokens, ascending intra-block id
+          for (int u = 0; u < PBK; ++u) {
+            if (keepflag[u]) continue;
+            const u32x4 pv = *reinterpret_cast<const u32x4*>(dOh + (int64_t)(origin + koff[u]) * D + ch);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              gf[2 * e] += __uint_as_float(pv[e] << 16);
+              gf[2 * e + 1] += __uint_as_float(pv[e] & 0xffff0000u);
+            }
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e) gv[e] = pack_bf16(gf[2 * e], gf[2 * e + 1]);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          dsum += gf[2 * e] * __uint_as_float(ov[e] << 16);
+          dsum += gf[2 * e + 1] * __uint_as_float(ov[e] & 0xffff0000u);
+        }
+      }
+      const int pos = (ch >> 3) ^ swz<D>(q);  // chunk position inside the swizzled row
+      *reinterpret_cast<u32x4*>(rec + R::QC + q * R::RB + pos * 16) = qv;
+      *reinterpret_cast<u32x4*>(rec + R::GC + q * R::RB + pos * 16) = gv;
+    }
+    dpart[q][part] = dsum;
+  }
+  __syncthreads();
+  if (tid < R::NQ) {
+    const int tok = qtok[tid];
+    reinterpret_cast<float*>(rec + R::LS)[tid] = tok >= 0 ? Lh[tok] * kLog2e : INFINITY;  // padding rows: exp2(x - inf) = 0
+    reinterpret_cast<float*>(rec + R::DL)[tid] = tok >= 0 ? (dpart[tid][0] + dpart[tid][1]) + (dpart[tid][2] + dpart[tid][3]) : 0.f;
+  }
+}
+
+// ------------------------------------------------------------------------------- dQ
+template <int D, bool SPLITQ>
+__global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom g, AttnArgs a) {
+  using R = BwdRec<D, SPLITQ ? 2 : 1>;
+  constexpr int NT = SPLITQ ? 512 : 256;
+  constexpr int NB = SPLITQ ? 4 : 2;
+  constexpr int RB = D * 2, CPR = D / 8, TILE = PBK * RB, NI = PBK * CPR / NT;
+  constexpr int DT = D / 32, DS = D / 16;
+  extern __shared__ __align__(16) uint8_t smem[];
+  uint8_t* ring = smem;                                                  // [NB][K tile | V tile]
+  uint32_t* masks = reinterpret_cast<uint32_t*>(smem + NB * 2 * TILE);   // [PG][W]
+  __shared__ int koff[PBK];
+  __shared__ uint32_t keepbits[PG][2];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = lane >> 5, col = lane & 31;
+  const int qb = wave & 3, sub = wave >> 2;
+  const int ngroups = (g.N + PG - 1) / PG;
+  const int unit = xcd_remap8(blockIdx.x, gridDim.x);
+  const int64_t bh = unit / ngroups;
+  const int i = (unit % ngroups) * PG + qb;
+  const bool valid = i < g.N;
+  const int64_t row = bh * g.N + i;
+  const int W = (g.N + 31) / 32;
+  const uint16_t* Kh = static_cast<const uint16_t*>(a.K) + bh * g.L * D;
+  const uint16_t* Vh = static_cast<const uint16_t*>(a.V) + bh * g.L * D;
+  uint16_t* dQh = static_cast<uint16_t*>(a.dQ) + bh * g.L * D;
+  const uint8_t* rec = static_cast<const uint8_t*>(a.ws) + row * (int64_t)R::BYTES;
+
+  if (tid < PBK) koff[tid] = intra_offset(g, tid);
+  for (int k = tid; k < PG * W; k += NT) masks[k] = 0u;
+  if (tid < 2 * PG) keepbits[tid >> 1][tid & 1] = 0u;
+  __syncthreads();
+  if (valid && sub == 0) {
+    if (g.dense) {
+      for (int w = lane; w < W; w += 64)
+        masks[qb * W + w] = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
+    } else {
+      const int beg = a.q2k_ptr[row], cnt = a.q2k_ptr[row + 1] - beg;
+      for (int t = lane; t < cnt; t += 64) {
+        const int j = a.q2k_idx[beg + t];
+        if ((unsigned)j < (unsigned)g.N) atomicOr(&masks[qb * W + (j >> 5)], 1u << (j & 31));
+      }
+    }
+  }
+  int goff[NI];
+#pragma unroll
+  for (int n = 0; n < NI; ++n) {
+    const int slot = tid + NT * n, r = slot / CPR, c = (slot % CPR) ^ swz<D>(r);
+    goff[n] = koff[r] * D + c * 8;
+  }
+  auto issue = [&](int jb, int b) {
+    const int64_t origin = (int64_t)block_origin_fast(g, jb) * D;
+    uint8_t* kdst = ring + b * 2 * TILE + wave * 1024;
+#pragma unroll
+    for (int n = 0; n < NI; ++n) dma16(Kh + origin + goff[n], kdst + n * (NT * 16));
+#pragma unroll
+    for (int n = 0; n < NI; ++n) dma16(Vh + origin + goff[n], kdst + TILE + n * (NT * 16));
+  };
+
+  // Q^T and G^T fragments (B operands) and the row constants, from the query block's record
+  const int qpos = 32 * sub + col;
+  int qid = -1, qtok = 0;
+  float lse2 = INFINITY, delta = 0.f;
+  if (valid && qpos < a.n_keep) {
+    qid = g.dense ? qpos : min(max(a.keep_idx[row * a.n_keep + qpos], 0), PBK - 1);
+    qtok = block_origin(g, i) + koff[qid];
+    atomicOr(&keepbits[qb][qid >> 5], 1u << (qid & 31));
+    lse2 = reinterpret_cast<const float*>(rec + R::LS)[qpos];
+    delta = reinterpret_cast<const float*>(rec + R::DL)[qpos];
+  }
+  bf16x8 qf[DS], gf[DS];
+#pragma unroll
+  for (int s = 0; s < DS; ++s) {
+    u32x4 qv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
+    if (qid >= 0) {
+      const int off = qpos * RB + (((2 * s + grp) ^ swz<D>(qpos)) << 4);
+      qv = *reinterpret_cast<const u32x4*>(rec + R::QC + off);
+      gv = *reinterpret_cast<const u32x4*>(rec + R::GC + off);
+    }
+    qf[s] = as_frag(qv);
+    gf[s] = as_frag(gv);
+  }
+  settle(lse2);
+  settle(delta);
+#pragma unroll
+  for (int s = 0; s < DS; ++s) {
+    settle(qf[s]);
+    settle(gf[s]);
+  }
+
+  int koffs[DS];
+#pragma unroll
+  for (int s = 0; s < DS; ++s) koffs[s] = col * RB + (((2 * s + grp) ^ swz<D>(col)) << 4);
+  const int L16 = lane & 15, q16 = lane >> 4, rsub = L16 >> 2, jj = L16 & 3;
+  const int cl = 2 * (q16 & 1) + (jj >> 1), rhi = D == 128 ? rsub : (rsub >> 1);
+  int voffs[2][DT];
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      voffs[h][dt] = (8 * h + 4 * grp + rsub) * RB + ((((dt ^ rhi) << 2) | (cl ^ (2 * h + grp))) << 4) + 8 * (jj & 1);
+
+  f32x16 dq[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
+  const float c2 = a.sm_scale * kLog2e;
+  __syncthreads();
+
+  Walk4 walk(masks, W, qb);
+  int issued = 0;
+  uint32_t pending = 0;
+  {
+#pragma unroll
+    for (int k = 0; k < NB - 1; ++k) {
+      bool mk = false;
+      const int jb = walk.next(mk);
+      if (jb >= 0) {
+        issue(jb, k);
+        pending |= (mk ? 1u : 0u) << k;
+        ++issued;
+      }
+    }
+  }
+  for (int t = 0; t < issued; ++t) {
+    const int ahead = issued - t - 1;
+    if (NB >= 4 && ahead >= 2) {
+      if (2 * NI == 4) BSA_WAIT_VM(8); else BSA_WAIT_VM(4);
+    } else if (NB >= 3 && ahead == 1) {
+      if (2 * NI == 4) BSA_WAIT_VM(4); else BSA_WAIT_VM(2);
+    } else {
+      BSA_WAIT_VM(0);
+    }
+    raw_barrier();
+    {
+      bool mn = false;
+      const int jn = walk.next(mn);
+      if (jn >= 0) {
+        issue(jn, (t + NB - 1) & (NB - 1));
+        pending |= (mn ? 1u : 0u) << (NB - 1);
+        ++issued;
+      }
+    }
+    const bool mine = pending & 1u;
+    pending >>= 1;
+    if (mine) {
+      const uint8_t* Kb = ring + (t & (NB - 1)) * 2 * TILE;
+      const uint8_t* Vb = Kb + TILE;
+      // one key half (32 keys) at a time: 2*DS row fragments (K, V alternating), then 2*DT
+      // transposed K fragments; a ring of RING register fragments runs ahead of the MFMAs
+      constexpr int RING = 8, NF = 2 * DS + 2 * DT;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        auto frag = [&](int f) -> bf16x8 {
+          if (f < 2 * DS) {
+            const uint8_t* base = (f & 1) ? Vb : Kb;
+            return lds_frag(reinterpret_cast<const uint16_t*>(base + 32 * kt * RB + koffs[f >> 1]));
+          }
+          const int v = f - 2 * DS, h = v / DT, dt = v % DT, ks = 2 * kt + h;
+          return lds_frag_tr(Kb + voffs[0][dt] + 16 * ks * RB, Kb + voffs[1][dt] + 16 * ks * RB);
+        };
+        bf16x8 fr[RING];
+#pragma unroll
+        for (int f = 0; f < RING; ++f) fr[f] = frag(f);
+        BSA_FENCE();
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+#pragma unroll
+        for (int f = 0; f < 2 * DS; ++f) {
+          if (f & 1) dp = mfma32(fr[f % RING], gf[f >> 1], dp);
+          else s = mfma32(fr[f % RING], qf[f >> 1], s);
+          if (f + RING < NF) fr[f % RING] = frag(f + RING);
+          if (f & 1) BSA_FENCE();
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c2, -lse2));
+          s[r] = p * (dp[r] - delta);
+        }
+        const bf16x8 d0 = d_to_b(s, 0), d1 = d_to_b(s, 1);
+        BSA_FENCE();
+#pragma unroll
+        for (int f = 2 * DS; f < NF; ++f) {
+          const int v = f - 2 * DS;
+          dq[v % DT] = mfma32(fr[f % RING], (v / DT) ? d1 : d0, dq[v % DT]);
+          if (f + RING < NF) fr[f % RING] = frag(f + RING);
+          if (f & 1) BSA_FENCE();
+        }
+      }
+    }
+  }
+
+  if (qid >= 0) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        u32x2 v;
+        v.x = pack_bf16(dq[dt][4 * r4 + 0] * a.sm_scale, dq[dt][4 * r4 + 1] * a.sm_scale);
+        v.y = pack_bf16(dq[dt][4 * r4 + 2] * a.sm_scale, dq[dt][4 * r4 + 3] * a.sm_scale);
+        *reinterpret_cast<u32x2*>(dQh + (int64_t)qtok * D + 32 * dt + 8 * r4 + 4 * grp) = v;
+      }
+  }
+  __syncthreads();
+  // pruned queries take no part in the forward: zero gradient rows
+  if (valid && !g.dense && sub == 0) {
+    const bool kept = (keepbits[qb][lane >> 5] >> (lane & 31)) & 1u;
+    if (!kept) {
+      const int64_t tok = block_origin(g, i) + koff[lane];
+      const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int q = 0; q < D / 8; ++q) *reinterpret_cast<u32x4*>(dQh + tok * D + 8 * q) = z;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------ dK, dV
+struct Walk2 {  // ascending walk over the union of two lists (bit masks in LDS), scalar state
+  const uint32_t* masks;  // [2][W]
+  int W, own_list, word;
+  uint32_t u, own;
+  __device__ inline Walk2(const uint32_t* m, int W_, int own_) : masks(m), W(W_), own_list(own_), word(-1), u(0), own(0) {}
+  __device__ inline int next(bool& mine) {
+    while (u == 0) {
+      if (++word >= W) return -1;
+      u = __builtin_amdgcn_readfirstlane(masks[word] | masks[W + word]);
+      own = __builtin_amdgcn_readfirstlane(masks[own_list * W + word]);
+    }
+    const int b = __builtin_ctz(u);
+    u &= u - 1;
+    mine = (own >> b) & 1u;
+    return word * 32 + b;
+  }
+};
+
+// wait until at most `n` DMA instructions of this wavefront are outstanding (n = per_tile * ahead)
+#define BSA_WAIT_CASE(k) case k: BSA_WAIT_VM(k); break;
+__device__ inline void wait_vm_upto(int n) {
+  switch (n) {
+    BSA_WAIT_CASE(0) BSA_WAIT_CASE(4) BSA_WAIT_CASE(5) BSA_WAIT_CASE(8) BSA_WAIT_CASE(9) BSA_WAIT_CASE(10)
+    BSA_WAIT_CASE(12) BSA_WAIT_CASE(15) BSA_WAIT_CASE(16) BSA_WAIT_CASE(18) BSA_WAIT_CASE(20) BSA_WAIT_CASE(24)
+    BSA_WAIT_CASE(25) BSA_WAIT_CASE(27) BSA_WAIT_CASE(30) BSA_WAIT_CASE(36) BSA_WAIT_CASE(45) BSA_WAIT_CASE(54)
+    default: BSA_WAIT_VM(0); break;
+  }
+}
+
+template <int D, int NQT>
+__global__ __launch_bounds__(256, 2) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a) {
+  using R = BwdRec<D, NQT>;
+  constexpr int RB = D * 2, CPR = D / 8, TILE = PBK * RB, DT = D / 32, DS = D / 16;
+  constexpr int NB = NQT == 1 ? 4 : 2;                 // ring depth (records)
+  constexpr int NFULL = R::CHUNKS / 256;               // DMA instructions every wavefront issues per record
+  constexpr int NTAIL = R::CHUNKS % 256;               // chunks of the last, partial instruction (wavefront 0 only)
+  constexpr int NI = PBK * CPR / 256;                  // DMA instructions per thread per stationary K (or V) tile
+  static_assert(NTAIL <= 64, "record tail must fit one wavefront");
+  extern __shared__ __align__(16) uint8_t smem[];
+  uint8_t* kvst = smem;                                                    // [2 KV blocks][K tile | V tile], stationary
+  uint8_t* ring = smem + 4 * TILE;                                         // [NB][record]
+  uint32_t* masks = reinterpret_cast<uint32_t*>(ring + NB * R::BYTES);     // [2][W]
+  __shared__ int koff[PBK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = lane >> 5, col = lane & 31;
+  const int which = wave >> 1, half = wave & 1;
+  const int npairs = (g.N + 1) / 2;
+  const int unit = xcd_remap8(blockIdx.x, gridDim.x);
+  const int64_t bh = unit / npairs;
+  const int j0 = (unit % npairs) * 2;
+  const int j = j0 + which;  // this wavefront's KV block; it owns keys 32*half .. +31
+  const bool valid = j < g.N;
+  const int64_t colrow = bh * g.N + j;
+  const int W = (g.N + 31) / 32;
+  const uint16_t* Kh = static_cast<const uint16_t*>(a.K) + bh * g.L * D;
+  const uint16_t* Vh = static_cast<const uint16_t*>(a.V) + bh * g.L * D;
+  uint16_t* dKh = static_cast<uint16_t*>(a.dK) + bh * g.L * D;
+  uint16_t* dVh = static_cast<uint16_t*>(a.dV) + bh * g.L * D;
+  const uint8_t* ws = static_cast<const uint8_t*>(a.ws) + bh * g.N * (int64_t)R::BYTES;
+
+  if (tid < PBK) koff[tid] = intra_offset(g, tid);
+  for (int k = tid; k < 2 * W; k += 256) masks[k] = 0u;
+  __syncthreads();
+  if (valid && half == 0) {
+    if (g.dense) {
+      for (int w = lane; w < W; w += 64)
+        masks[which * W + w] = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
+    } else {
+      const int beg = a.k2q_ptr[colrow], cnt = a.k2q_ptr[colrow + 1] - beg;
+      for (int t = lane; t < cnt; t += 64) {
+        const int ib = a.k2q_idx[beg + t];
+        if ((unsigned)ib < (unsigned)g.N) atomicOr(&masks[which * W + (ib >> 5)], 1u << (ib & 31));
+      }
+    }
+  }
+  // The K and V tiles of the workgroup's two KV blocks stay in LDS for the whole walk (their
+  // fragments are the B operands of S and dP); keeping them in registers instead pushes the
+  // kernel past 256 VGPRs and the compiler then shuttles accumulators between register files.
+  for (int blk = 0; blk < 2; ++blk) {
+    const int jb = min(j0 + blk, g.N - 1);
+    const int64_t origin = (int64_t)block_origin(g, jb) * D;
+#pragma unroll
+    for (int n = 0; n < NI; ++n) {
+      const int slot = tid + 256 * n, r = slot / CPR, c = (slot % CPR) ^ swz<D>(r);
+      const int off = koff[r] * D + c * 8;
+      dma16(Kh + origin + off, kvst + blk * 2 * TILE + wave * 1024 + n * 4096);
+      dma16(Vh + origin + off, kvst + blk * 2 * TILE + TILE + wave * 1024 + n * 4096);
+    }
+  }
+  const int64_t ktok = valid ? block_origin(g, j) + koff[32 * half + col] : 0;
+  int koffs[DS];
+#pragma unroll
+  for (int s = 0; s < DS; ++s) koffs[s] = col * RB + (((2 * s + grp) ^ swz<D>(col)) << 4);
+  const int L16 = lane & 15, q16 = lane >> 4, rsub = L16 >> 2, jj = L16 & 3;
+  const int cl = 2 * (q16 & 1) + (jj >> 1), rhi = D == 128 ? rsub : (rsub >> 1);
+  int voffs[2][DT];
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      voffs[h][dt] = (8 * h + 4 * grp + rsub) * RB + ((((dt ^ rhi) << 2) | (cl ^ (2 * h + grp))) << 4) + 8 * (jj & 1);
+
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dk[dt][r] = dv[dt][r] = 0.f;
+  const float c2 = a.sm_scale * kLog2e;
+  const int per_tile = NFULL + (wave == 0 && NTAIL ? 1 : 0);  // DMA instructions of this wavefront per record
+  const uint8_t* Kst = kvst + which * 2 * TILE + 32 * half * RB;  // this wavefront's 32 K rows; V rows at + TILE
+  BSA_WAIT_VM(0);
+  __syncthreads();
+
+  auto issue = [&](int ib, int b) {
+    const uint8_t* src = ws + ib * (int64_t)R::BYTES + tid * 16;
+    uint8_t* dst = ring + b * R::BYTES + wave * 1024;
+#pragma unroll
+    for (int n = 0; n < NFULL; ++n) dma16(src + n * 4096, dst + n * 4096);
+    if (NTAIL && wave == 0 && lane < NTAIL) dma16(src + NFULL * 4096, dst + NFULL * 4096);
+  };
+  Walk2 walk(masks, W, which);
+  int issued = 0;
+  uint32_t pending = 0;
+  {
+#pragma unroll
+    for (int k = 0; k < NB - 1; ++k) {
+      bool mk = false;
+      const int ib = walk.next(mk);
+      if (ib >= 0) {
+        issue(ib, k);
+        pending |= (mk ? 1u : 0u) << k;
+        ++issued;
+      }
+    }
+  }
+  for (int t = 0; t < issued; ++t) {
+    wait_vm_upto(per_tile * (issued - t - 1));
+    raw_barrier();
+    {
+      bool mn = false;
+      const int in = walk.next(mn);
+      if (in >= 0) {
+        issue(in, (t + NB - 1) & (NB - 1));
+        pending |= (mn ? 1u : 0u) << (NB - 1);
+        ++issued;
+      }
+    }
+    const bool mine = pending & 1u;
+    pending >>= 1;
+    if (mine) {
+      const uint8_t* rb = ring + (t & (NB - 1)) * R::BYTES;
+      const uint8_t* Qc = rb + R::QC;
+      const uint8_t* Gc = rb + R::GC;
+      const float* ls = reinterpret_cast<const float*>(rb + R::LS);
+      const float* dl = reinterpret_cast<const float*>(rb + R::DL);
+#pragma unroll
+      for (int qt = 0; qt < NQT; ++qt) {
+        // fragments in use order: per k-step (Qc row, K row, Gc row, V row), then per
+        // (16-query step, channel tile) (Gc^T, Qc^T); a ring of RING fragments runs ahead
+        constexpr int RING = 8, NF = 4 * DS + 4 * DT;
+        auto frag = [&](int f) -> bf16x8 {
+          if (f < 4 * DS) {
+            const int sp = f >> 2, kind = f & 3;
+            const uint8_t* base = kind == 0 ? Qc + 32 * qt * RB : kind == 1 ? Kst : kind == 2 ? Gc + 32 * qt * RB : Kst + TILE;
+            return lds_frag(reinterpret_cast<const uint16_t*>(base + koffs[sp]));
+          }
+          const int v = f - 4 * DS, dt = (v >> 1) % DT, h = (v >> 1) / DT, ks = 2 * qt + h;
+          const uint8_t* base = (v & 1) ? Qc : Gc;
+          return lds_frag_tr(base + voffs[0][dt] + 16 * ks * RB, base + voffs[1][dt] + 16 * ks * RB);
+        };
+        bf16x8 fr[RING];
+#pragma unroll
+        for (int f = 0; f < RING; ++f) fr[f] = frag(f);
+        BSA_FENCE();
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+#pragma unroll
+        for (int f = 0; f < 4 * DS; f += 2) {
+          if (f & 2) dp = mfma32(fr[f % RING], fr[(f + 1) % RING], dp);
+          else s = mfma32(fr[f % RING], fr[(f + 1) % RING], s);
+          if (f + RING < NF) fr[f % RING] = frag(f + RING);
+          if (f + 1 + RING < NF) fr[(f + 1) % RING] = frag(f + 1 + RING);
+          if (f & 2) BSA_FENCE();
+        }
+        // D layout: lane = key column, register r = query row 32*qt + 8*(r/4) + 4*grp + r%4
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(ls + 32 * qt + 8 * r4 + 4 * grp);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dl + 32 * qt + 8 * r4 + 4 * grp);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * r4 + e], c2, -l4[e]));
+            s[4 * r4 + e] = p;
+            dp[4 * r4 + e] = p * (dp[4 * r4 + e] - d4[e]);
+          }
+        }
+        const bf16x8 pf0 = d_to_b(s, 0), pf1 = d_to_b(s, 1), df0 = d_to_b(dp, 0), df1 = d_to_b(dp, 1);
+        BSA_FENCE();
+#pragma unroll
+        for (int f = 4 * DS; f < NF; ++f) {
+          const int v = f - 4 * DS, dt = (v >> 1) % DT, h = (v >> 1) / DT;
+          if (v & 1) dk[dt] = mfma32(fr[f % RING], h ? df1 : df0, dk[dt]);
+          else dv[dt] = mfma32(fr[f % RING], h ? pf1 : pf0, dv[dt]);
+          if (f + RING < NF) fr[f % RING] = frag(f + RING);
+          if (f & 1) BSA_FENCE();
+        }
+      }
+    }
+  }
+  if (valid) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        u32x2 kv, vv;
+        kv.x = pack_bf16(dk[dt][4 * r4 + 0] * a.sm_scale, dk[dt][4 * r4 + 1] * a.sm_scale);
+        kv.y = pack_bf16(dk[dt][4 * r4 + 2] * a.sm_scale, dk[dt][4 * r4 + 3] * a.sm_scale);
+        vv.x = pack_bf16(dv[dt][4 * r4 + 0], dv[dt][4 * r4 + 1]);
+        vv.y = pack_bf16(dv[dt][4 * r4 + 2], dv[dt][4 * r4 + 3]);
+        const int ch = 32 * dt + 8 * r4 + 4 * grp;
+        *reinterpret_cast<u32x2*>(dKh + ktok * D + ch) = kv;
+        *reinterpret_cast<u32x2*>(dVh + ktok * D + ch) = vv;
+      }
+  }
+}
+
+template <int D, int NQT>
+static int launch_bwd_pipe_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
+  using R = BwdRec<D, NQT>;
+  constexpr bool SPLITQ = NQT == 2;
+  const int W = (g.N + 31) / 32;
+  if (a.stages & BSA_BWD_PRE) hipLaunchKernelGGL((bwd_pre_pipe_kernel<D, NQT>), dim3(g.rows), dim3(256), 0, st, g, a);
+  const size_t lds_q = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PG * W * 4;
+  const size_t lds_kv = (size_t)4 * PBK * D * 2 + (size_t)(NQT == 1 ? 4 : 2) * R::BYTES + (size_t)2 * W * 4;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_pipe_kernel<D, SPLITQ>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_pipe_kernel<D, NQT>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv) != hipSuccess)
+    return BSA_ERR_LAUNCH;
+  if (a.stages & BSA_BWD_DQ)
+    hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ>), dim3(((g.N + PG - 1) / PG) * g.B * g.H), dim3(SPLITQ ? 512 : 256),
+                       lds_q, st, g, a);
+  if (a.stages & BSA_BWD_DKV)
+    hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D, NQT>), dim3(((g.N + 1) / 2) * g.B * g.H), dim3(256), lds_kv, st, g, a);
+  return check_launch();
+}
+
+int launch_bwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st) {
+  const bool two = a.n_keep > 32;
+  if (g.d == 128) return two ? launch_bwd_pipe_t<128, 2>(g, a, st) : launch_bwd_pipe_t<128, 1>(g, a, st);
+  return two ? launch_bwd_pipe_t<64, 2>(g, a, st) : launch_bwd_pipe_t<64, 1>(g, a, st);
+}
+
+size_t bwd_workspace_pipe(const Geom& g, int n_keep) {
+  const bool two = n_keep > 32;
+  const size_t per_row = g.d == 128 ? (two ? BwdRec<128, 2>::BYTES : BwdRec<128, 1>::BYTES)
+                                    : (two ? BwdRec<64, 2>::BYTES : BwdRec<64, 1>::BYTES);
+  return per_row * (size_t)g.rows;
+}
+
 template <int D, bool SPLITQ>
 static int launch_fwd_pipe_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
   const int W = (g.N + 31) / 32;

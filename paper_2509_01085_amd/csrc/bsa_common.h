@@ -105,6 +105,8 @@ bool mfma_supported(const Geom& g, int dtype, int n_keep);
 int launch_fwd_mfma(const Geom& g, const AttnArgs& a, hipStream_t st);
 int launch_bwd_mfma(const Geom& g, const AttnArgs& a, hipStream_t st);
 size_t bwd_workspace_mfma(const Geom& g, int n_keep);
-int launch_fwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st);  // DMA-ring forward, same shapes
+int launch_fwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st);  // DMA-ring kernels, same shapes
+int launch_bwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st);
+size_t bwd_workspace_pipe(const Geom& g, int n_keep);
 
 }  // namespace bsa
