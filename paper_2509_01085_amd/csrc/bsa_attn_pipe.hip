@@ -668,31 +668,44 @@ struct Walk2 {  // ascending walk over the union of two lists (bit masks in LDS)
 #define BSA_WAIT_CASE(k) case k: BSA_WAIT_VM(k); break;
 __device__ inline void wait_vm_upto(int n) {
   switch (n) {
-    BSA_WAIT_CASE(0) BSA_WAIT_CASE(4) BSA_WAIT_CASE(5) BSA_WAIT_CASE(8) BSA_WAIT_CASE(9) BSA_WAIT_CASE(10)
+    BSA_WAIT_CASE(0) BSA_WAIT_CASE(1) BSA_WAIT_CASE(2) BSA_WAIT_CASE(3) BSA_WAIT_CASE(4) BSA_WAIT_CASE(5) BSA_WAIT_CASE(6) BSA_WAIT_CASE(8) BSA_WAIT_CASE(9) BSA_WAIT_CASE(10)
     BSA_WAIT_CASE(12) BSA_WAIT_CASE(15) BSA_WAIT_CASE(16) BSA_WAIT_CASE(18) BSA_WAIT_CASE(20) BSA_WAIT_CASE(24)
     BSA_WAIT_CASE(25) BSA_WAIT_CASE(27) BSA_WAIT_CASE(30) BSA_WAIT_CASE(36) BSA_WAIT_CASE(45) BSA_WAIT_CASE(54)
     default: BSA_WAIT_VM(0); break;
   }
 }
 
+template <int NQT>
+struct DkvRing {  // record ring of the dK/dV kernel
+  static constexpr int NB = NQT == 1 ? 5 : 2;   // depth
+  static constexpr int PER = NQT == 1 ? 2 : 1;  // records consumed per step
+};
+
 template <int D, int NQT>
-__global__ __launch_bounds__(256, 2) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a) {
+__global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a) {
   using R = BwdRec<D, NQT>;
+  constexpr int NT = 512;
   constexpr int RB = D * 2, CPR = D / 8, TILE = PBK * RB, DT = D / 32, DS = D / 16;
-  constexpr int NB = NQT == 1 ? 4 : 2;                 // ring depth (records)
-  constexpr int NFULL = R::CHUNKS / 256;               // DMA instructions every wavefront issues per record
-  constexpr int NTAIL = R::CHUNKS % 256;               // chunks of the last, partial instruction (wavefront 0 only)
-  constexpr int NI = PBK * CPR / 256;                  // DMA instructions per thread per stationary K (or V) tile
+  constexpr int NB = DkvRing<NQT>::NB;                 // ring depth (records)
+  constexpr int PER = DkvRing<NQT>::PER;               // records consumed per step
+  constexpr int NFULL = R::CHUNKS / NT;                // DMA instructions every wavefront issues per record
+  constexpr int NTAIL = R::CHUNKS % NT;                // chunks of the last, partial instruction (wavefront 0 only)
+  constexpr int NI = PBK * CPR / NT;                   // DMA instructions per thread per stationary K (or V) tile
   static_assert(NTAIL <= 64, "record tail must fit one wavefront");
+  static_assert(NB * R::BYTES >= 4 * DT * 16 * 256, "the ring doubles as the reduction buffer");
   extern __shared__ __align__(16) uint8_t smem[];
   uint8_t* kvst = smem;                                                    // [2 KV blocks][K tile | V tile], stationary
   uint8_t* ring = smem + 4 * TILE;                                         // [NB][record]
   uint32_t* masks = reinterpret_cast<uint32_t*>(ring + NB * R::BYTES);     // [2][W]
   __shared__ int koff[PBK];
 
+  // Eight wavefronts: (KV block, key half) x parity.  The two wavefronts of one (block, half)
+  // share a SIMD and take alternate records (n_keep <= 32) or the two query sub-tiles of each
+  // record (n_keep > 32), each with private accumulators that are summed at the end; while
+  // one waits for LDS or runs its softmax arithmetic the other keeps the matrix core busy.
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = lane >> 5, col = lane & 31;
-  const int which = wave >> 1, half = wave & 1;
+  const int par = wave >> 2, which = (wave >> 1) & 1, half = wave & 1;
   const int npairs = (g.N + 1) / 2;
   const int unit = xcd_remap8(blockIdx.x, gridDim.x);
   const int64_t bh = unit / npairs;
@@ -708,9 +721,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
   const uint8_t* ws = static_cast<const uint8_t*>(a.ws) + bh * g.N * (int64_t)R::BYTES;
 
   if (tid < PBK) koff[tid] = intra_offset(g, tid);
-  for (int k = tid; k < 2 * W; k += 256) masks[k] = 0u;
+  for (int k = tid; k < 2 * W; k += NT) masks[k] = 0u;
   __syncthreads();
-  if (valid && half == 0) {
+  if (valid && half == 0 && par == 0) {
     if (g.dense) {
       for (int w = lane; w < W; w += 64)
         masks[which * W + w] = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
@@ -730,10 +743,10 @@ __global__ __launch_bounds__(256, 2) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
     const int64_t origin = (int64_t)block_origin(g, jb) * D;
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
-      const int slot = tid + 256 * n, r = slot / CPR, c = (slot % CPR) ^ swz<D>(r);
+      const int slot = tid + NT * n, r = slot / CPR, c = (slot % CPR) ^ swz<D>(r);
       const int off = koff[r] * D + c * 8;
-      dma16(Kh + origin + off, kvst + blk * 2 * TILE + wave * 1024 + n * 4096);
-      dma16(Vh + origin + off, kvst + blk * 2 * TILE + TILE + wave * 1024 + n * 4096);
+      dma16(Kh + origin + off, kvst + blk * 2 * TILE + wave * 1024 + n * (NT * 16));
+      dma16(Vh + origin + off, kvst + blk * 2 * TILE + TILE + wave * 1024 + n * (NT * 16));
     }
   }
   const int64_t ktok = valid ? block_origin(g, j) + koff[32 * half + col] : 0;
@@ -757,6 +770,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
   const float c2 = a.sm_scale * kLog2e;
   const int per_tile = NFULL + (wave == 0 && NTAIL ? 1 : 0);  // DMA instructions of this wavefront per record
   const uint8_t* Kst = kvst + which * 2 * TILE + 32 * half * RB;  // this wavefront's 32 K rows; V rows at + TILE
+  const int qt = NQT == 1 ? 0 : par;                              // query sub-tile of a record this wavefront takes
   BSA_WAIT_VM(0);
   __syncthreads();
 
@@ -764,100 +778,130 @@ __global__ __launch_bounds__(256, 2) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
     const uint8_t* src = ws + ib * (int64_t)R::BYTES + tid * 16;
     uint8_t* dst = ring + b * R::BYTES + wave * 1024;
 #pragma unroll
-    for (int n = 0; n < NFULL; ++n) dma16(src + n * 4096, dst + n * 4096);
-    if (NTAIL && wave == 0 && lane < NTAIL) dma16(src + NFULL * 4096, dst + NFULL * 4096);
+    for (int n = 0; n < NFULL; ++n) dma16(src + n * (NT * 16), dst + n * (NT * 16));
+    if (NTAIL && wave == 0 && lane < NTAIL) dma16(src + NFULL * (NT * 16), dst + NFULL * (NT * 16));
   };
+  auto modnb = [](int x) { return x >= NB ? x - NB : x; };
   Walk2 walk(masks, W, which);
-  int issued = 0;
-  uint32_t pending = 0;
-  {
+  int issued = 0;        // records requested so far (positions of the union walk)
+  uint32_t pending = 0;  // bit k: position PER*s + k is on this wavefront's list
 #pragma unroll
-    for (int k = 0; k < NB - 1; ++k) {
+  for (int k = 0; k < NB - PER; ++k) {
+    bool mk = false;
+    const int ib = walk.next(mk);
+    if (ib >= 0) {
+      issue(ib, k);
+      pending |= (mk ? 1u : 0u) << k;
+      ++issued;
+    }
+  }
+  int sc = 0;  // ring slot of position PER*s
+  for (int s = 0; PER * s < issued; ++s) {
+    // the records of this step have landed once at most the later requests are outstanding
+    wait_vm_upto(per_tile * max(0, issued - PER * (s + 1)));
+    raw_barrier();  // ... for every wavefront; and every wavefront is done with the previous step's slots
+#pragma unroll
+    for (int k = NB - PER; k < NB; ++k) {
       bool mk = false;
       const int ib = walk.next(mk);
       if (ib >= 0) {
-        issue(ib, k);
+        issue(ib, modnb(sc + k));
         pending |= (mk ? 1u : 0u) << k;
         ++issued;
       }
     }
-  }
-  for (int t = 0; t < issued; ++t) {
-    wait_vm_upto(per_tile * (issued - t - 1));
-    raw_barrier();
-    {
-      bool mn = false;
-      const int in = walk.next(mn);
-      if (in >= 0) {
-        issue(in, (t + NB - 1) & (NB - 1));
-        pending |= (mn ? 1u : 0u) << (NB - 1);
-        ++issued;
-      }
-    }
-    const bool mine = pending & 1u;
-    pending >>= 1;
+    const int kpos = NQT == 1 ? par : 0;
+    const bool mine = (pending >> kpos) & 1u;
+    pending >>= PER;
     if (mine) {
-      const uint8_t* rb = ring + (t & (NB - 1)) * R::BYTES;
+      const uint8_t* rb = ring + modnb(sc + kpos) * R::BYTES;
       const uint8_t* Qc = rb + R::QC;
       const uint8_t* Gc = rb + R::GC;
       const float* ls = reinterpret_cast<const float*>(rb + R::LS);
       const float* dl = reinterpret_cast<const float*>(rb + R::DL);
-#pragma unroll
-      for (int qt = 0; qt < NQT; ++qt) {
-        // fragments in use order: per k-step (Qc row, K row, Gc row, V row), then per
-        // (16-query step, channel tile) (Gc^T, Qc^T); a ring of RING fragments runs ahead
-        constexpr int RING = 8, NF = 4 * DS + 4 * DT;
-        auto frag = [&](int f) -> bf16x8 {
-          if (f < 4 * DS) {
-            const int sp = f >> 2, kind = f & 3;
-            const uint8_t* base = kind == 0 ? Qc + 32 * qt * RB : kind == 1 ? Kst : kind == 2 ? Gc + 32 * qt * RB : Kst + TILE;
-            return lds_frag(reinterpret_cast<const uint16_t*>(base + koffs[sp]));
-          }
-          const int v = f - 4 * DS, dt = (v >> 1) % DT, h = (v >> 1) / DT, ks = 2 * qt + h;
-          const uint8_t* base = (v & 1) ? Qc : Gc;
-          return lds_frag_tr(base + voffs[0][dt] + 16 * ks * RB, base + voffs[1][dt] + 16 * ks * RB);
-        };
-        bf16x8 fr[RING];
-#pragma unroll
-        for (int f = 0; f < RING; ++f) fr[f] = frag(f);
-        BSA_FENCE();
-        f32x16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
-#pragma unroll
-        for (int f = 0; f < 4 * DS; f += 2) {
-          if (f & 2) dp = mfma32(fr[f % RING], fr[(f + 1) % RING], dp);
-          else s = mfma32(fr[f % RING], fr[(f + 1) % RING], s);
-          if (f + RING < NF) fr[f % RING] = frag(f + RING);
-          if (f + 1 + RING < NF) fr[(f + 1) % RING] = frag(f + 1 + RING);
-          if (f & 2) BSA_FENCE();
+      // fragments in use order: per k-step (Qc row, K row, Gc row, V row), then per
+      // (16-query step, channel tile) (Gc^T, Qc^T); a ring of RING fragments runs ahead
+      constexpr int RING = 8, NF = 4 * DS + 4 * DT;
+      auto frag = [&](int f) -> bf16x8 {
+        if (f < 4 * DS) {
+          const int sp = f >> 2, kind = f & 3;
+          const uint8_t* base = kind == 0 ? Qc + 32 * qt * RB : kind == 1 ? Kst : kind == 2 ? Gc + 32 * qt * RB : Kst + TILE;
+          return lds_frag(reinterpret_cast<const uint16_t*>(base + koffs[sp]));
         }
-        // D layout: lane = key column, register r = query row 32*qt + 8*(r/4) + 4*grp + r%4
+        const int v = f - 4 * DS, dt = (v >> 1) % DT, h = (v >> 1) / DT;
+        const uint8_t* base = ((v & 1) ? Qc : Gc) + 16 * (2 * qt + h) * RB;
+        return lds_frag_tr(base + voffs[0][dt], base + voffs[1][dt]);
+      };
+      bf16x8 fr[RING];
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(ls + 32 * qt + 8 * r4 + 4 * grp);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(dl + 32 * qt + 8 * r4 + 4 * grp);
+      for (int f = 0; f < RING; ++f) fr[f] = frag(f);
+      BSA_FENCE();
+      f32x16 sacc, dp;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[4 * r4 + e], c2, -l4[e]));
-            s[4 * r4 + e] = p;
-            dp[4 * r4 + e] = p * (dp[4 * r4 + e] - d4[e]);
-          }
-        }
-        const bf16x8 pf0 = d_to_b(s, 0), pf1 = d_to_b(s, 1), df0 = d_to_b(dp, 0), df1 = d_to_b(dp, 1);
-        BSA_FENCE();
+      for (int r = 0; r < 16; ++r) sacc[r] = dp[r] = 0.f;
 #pragma unroll
-        for (int f = 4 * DS; f < NF; ++f) {
-          const int v = f - 4 * DS, dt = (v >> 1) % DT, h = (v >> 1) / DT;
-          if (v & 1) dk[dt] = mfma32(fr[f % RING], h ? df1 : df0, dk[dt]);
-          else dv[dt] = mfma32(fr[f % RING], h ? pf1 : pf0, dv[dt]);
-          if (f + RING < NF) fr[f % RING] = frag(f + RING);
-          if (f & 1) BSA_FENCE();
+      for (int f = 0; f < 4 * DS; f += 2) {
+        if (f & 2) dp = mfma32(fr[f % RING], fr[(f + 1) % RING], dp);
+        else sacc = mfma32(fr[f % RING], fr[(f + 1) % RING], sacc);
+        if (f + RING < NF) fr[f % RING] = frag(f + RING);
+        if (f + 1 + RING < NF) fr[(f + 1) % RING] = frag(f + 1 + RING);
+        if (f & 2) BSA_FENCE();
+      }
+      // D layout: lane = key column, register r = query row 32*qt + 8*(r/4) + 4*grp + r%4
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(ls + 32 * qt + 8 * r4 + 4 * grp);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dl + 32 * qt + 8 * r4 + 4 * grp);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * r4 + e], c2, -l4[e]));
+          sacc[4 * r4 + e] = pv;
+          dp[4 * r4 + e] = pv * (dp[4 * r4 + e] - d4[e]);
         }
       }
+      const bf16x8 pf0 = d_to_b(sacc, 0), pf1 = d_to_b(sacc, 1), df0 = d_to_b(dp, 0), df1 = d_to_b(dp, 1);
+      BSA_FENCE();
+#pragma unroll
+      for (int f = 4 * DS; f < NF; ++f) {
+        const int v = f - 4 * DS, dt = (v >> 1) % DT, h = (v >> 1) / DT;
+        if (v & 1) dk[dt] = mfma32(fr[f % RING], h ? df1 : df0, dk[dt]);
+        else dv[dt] = mfma32(fr[f % RING], h ? pf1 : pf0, dv[dt]);
+        if (f + RING < NF) fr[f % RING] = frag(f + RING);
+        if (f & 1) BSA_FENCE();
+      }
+    }
+    sc = modnb(sc + PER);
+  }
+  // sum the two parities' accumulators (fixed order), dK then dV, through the idle ring
+  BSA_WAIT_VM(0);
+  f32x4* red = reinterpret_cast<f32x4*>(ring) + (wave & 3) * (DT * 4 * 64) + lane;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    __syncthreads();
+    if (par == 1) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x16& acc = pass ? dv[dt] : dk[dt];
+          f32x4 v = {acc[4 * r4], acc[4 * r4 + 1], acc[4 * r4 + 2], acc[4 * r4 + 3]};
+          red[(dt * 4 + r4) * 64] = v;
+        }
+    }
+    __syncthreads();
+    if (par == 0) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4 v = red[(dt * 4 + r4) * 64];
+          f32x16& acc = pass ? dv[dt] : dk[dt];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[4 * r4 + e] += v[e];
+        }
     }
   }
-  if (valid) {
+  if (valid && par == 0) {
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -881,7 +925,7 @@ static int launch_bwd_pipe_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
   const int W = (g.N + 31) / 32;
   if (a.stages & BSA_BWD_PRE) hipLaunchKernelGGL((bwd_pre_pipe_kernel<D, NQT>), dim3(g.rows), dim3(256), 0, st, g, a);
   const size_t lds_q = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PG * W * 4;
-  const size_t lds_kv = (size_t)4 * PBK * D * 2 + (size_t)(NQT == 1 ? 4 : 2) * R::BYTES + (size_t)2 * W * 4;
+  const size_t lds_kv = (size_t)4 * PBK * D * 2 + (size_t)DkvRing<NQT>::NB * R::BYTES + (size_t)2 * W * 4;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_pipe_kernel<D, SPLITQ>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q) != hipSuccess ||
       hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_pipe_kernel<D, NQT>),
@@ -891,7 +935,7 @@ static int launch_bwd_pipe_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ>), dim3(((g.N + PG - 1) / PG) * g.B * g.H), dim3(SPLITQ ? 512 : 256),
                        lds_q, st, g, a);
   if (a.stages & BSA_BWD_DKV)
-    hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D, NQT>), dim3(((g.N + 1) / 2) * g.B * g.H), dim3(256), lds_kv, st, g, a);
+    hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D, NQT>), dim3(((g.N + 1) / 2) * g.B * g.H), dim3(512), lds_kv, st, g, a);
   return check_launch();
 }
 
