@@ -168,7 +168,7 @@ def main():
     dense_flops = 14.0 * wl.B * wl.H * wl.L * wl.L * wl.d
     # credited FLOPs per listed (query block, KV block) pair, in units of d*n_keep*Bk:
     # forward 4 (QK^T, PV); dK/dV kernel 8 (S, dP, dV, dK); dQ kernel 2 (its S/dP recompute is not credited)
-    kernels = {"fwd_mfma_kernel": ("attn_fwd", 4), "bwd_dkv_mfma_kernel": ("bwd_dkv", 8), "bwd_dq_mfma_kernel": ("bwd_dq", 2)}
+    kernels = {"fwd_pipe_kernel": ("attn_fwd", 4), "bwd_dkv_pipe_kernel": ("bwd_dkv", 8), "bwd_dq_pipe_kernel": ("bwd_dq", 2)}
     dominant = max(kernels, key=lambda k: parts[kernels[k][0]])
 
     def roof(kname):

@@ -16,7 +16,6 @@ SOURCES = [
     "bsa_pool_prune.hip",
     "bsa_select.hip",
     "bsa_attn_generic.hip",
-    "bsa_attn_mfma.hip",
     "bsa_attn_pipe.hip",
 ]
 # -ffp-contract=off: the decision kernels fix every rounding; packed-fp32 ops are disabled

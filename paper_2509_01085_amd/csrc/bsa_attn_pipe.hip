@@ -23,6 +23,10 @@ namespace bsa {
 constexpr int PG = 4;     // query blocks per workgroup
 constexpr int PBK = 64;   // tokens per block on this path
 
+bool mfma_supported(const Geom& g, int dtype, int n_keep) {
+  return dtype == BSA_BF16 && g.Bk == PBK && (g.d == 128 || g.d == 64) && n_keep <= PBK;
+}
+
 __device__ inline int xcd_remap8(int n, int total) {
   // workgroup n runs on XCD n % 8; give every XCD one contiguous range of units
   const int q = total >> 3, r = total & 7, x = n & 7;
@@ -194,20 +198,12 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
       bool mn = false;
       const int jn = walk.next(mn);
       if (jn >= 0) {
-#ifndef BSA_EXP_NOLOAD
         issue(jn, (t + NB - 1) & (NB - 1));
-#endif
         pending |= (mn ? 1u : 0u) << (NB - 1);
         ++issued;
       }
     }
-#ifdef BSA_EXP_NOCOMPUTE
-    const bool mine = false;
-#elif defined(BSA_EXP_ALLMINE)
-    const bool mine = true;
-#else
     const bool mine = pending & 1u;
-#endif
     pending >>= 1;
     if (mine) {
       // 64 keys x this wavefront's 32 queries.  The 4*DS A fragments of the tile (K rows for
@@ -321,10 +317,10 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
 //   dQ    the forward's walk (four query blocks per workgroup, union of their KV lists):
 //         S^T = K Q^T, dP^T = V G^T, dS^T = P^T (dP^T - delta), dQ^T += K^T dS^T, one key half
 //         at a time; K^T comes from the same K tile through transposed LDS reads.
-//   dKV   a workgroup owns two adjacent KV blocks (a wavefront 32 keys, with its K^T / V^T
-//         fragments resident in registers) and walks the union of their k2q lists; the
-//         query-block records stream through a deep LDS ring by DMA:
-//         S = Qc K^T, dP = Gc V^T, dV^T += Gc^T P, dK^T += Qc^T dS.
+//   dKV   a workgroup owns two adjacent KV blocks, whose K and V tiles stay in LDS, and walks
+//         the union of their k2q lists; the query-block records stream through an LDS ring
+//         by DMA.  A wavefront owns 32 keys: S = Qc K^T, dP = Gc V^T, dV^T += Gc^T P,
+//         dK^T += Qc^T dS, accumulators in registers for the whole walk.
 // =====================================================================================
 
 template <int D, int NQT>

@@ -101,11 +101,8 @@ int launch_bwd_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t 
 size_t bwd_workspace_generic(const Geom& g, int n_keep);
 
 // bf16 MFMA kernels: Bk == 64, d == 128 (or 64), n_keep <= 64
-bool mfma_supported(const Geom& g, int dtype, int n_keep);
-int launch_fwd_mfma(const Geom& g, const AttnArgs& a, hipStream_t st);
-int launch_bwd_mfma(const Geom& g, const AttnArgs& a, hipStream_t st);
-size_t bwd_workspace_mfma(const Geom& g, int n_keep);
-int launch_fwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st);  // DMA-ring kernels, same shapes
+bool mfma_supported(const Geom& g, int dtype, int n_keep);  // shapes the bf16 MFMA kernels cover
+int launch_fwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st);
 int launch_bwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st);
 size_t bwd_workspace_pipe(const Geom& g, int n_keep);
 

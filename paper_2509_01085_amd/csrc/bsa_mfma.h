@@ -38,24 +38,6 @@ __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// The same instruction with the accumulator pinned to accumulation registers (AGPRs).  For
-// kernels whose stationary state exceeds the 256 architectural VGPRs the compiler otherwise
-// shuttles accumulators between the two register files around every use (hundreds of
-// v_accvgpr moves per tile).  An accumulator only ever touched through this helper stays in
-// AGPRs for the whole loop; read it back after mfma_drain().
-__device__ inline void mfma32_pinned(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-// D (in VGPRs) += A * B with the stationary B operand pinned to AGPRs.
-__device__ inline void mfma32_bpinned(f32x16& d, bf16x8 a, bf16x8 b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
-}
-// software wait states the hazard rules ask for between a matrix instruction issued from
-// inline assembly and a vector instruction that reads its result
-__device__ inline void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
-// ... and between a vector instruction producing an operand and the pinned MFMA consuming it
-__device__ inline void mfma_operand_settle() { asm volatile("s_nop 3" ::: "memory"); }
-
 __device__ inline bf16x8 lds_frag(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
 __device__ inline bf16x8 as_frag(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
