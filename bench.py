@@ -26,6 +26,14 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
+# Bytes per launch between L2 and the memory side, from the rocprofv3 --pmc passes
+# (FETCH_SIZE, WRITE_SIZE, scaled by a 1 GiB copy's readings) recorded in profiles/bench_<workload>.md.
+# Hardware counters cannot be read from inside this process, so the figure is carried here.
+MEASURED_TRAFFIC_BYTES = {
+    ("wan1p3b", "bwd_dkv_pipe_kernel"): 3.45e9,
+    ("wan1p3b", "bwd_dq_pipe_kernel"): 10.02e9,
+    ("wan1p3b", "fwd_pipe_kernel"): 9.07e9,
+}
 
 
 def parse():
@@ -39,7 +47,10 @@ def parse():
     ap.add_argument("--keep-ratio", type=float, default=None)
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
-    ap.add_argument("--cpu-heads", type=int, default=1, help="heads of the workload the CPU oracle is timed on")
+    ap.add_argument("--cpu-heads", type=int, default=3, help="heads of the workload the CPU oracle is timed on")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain elementwise copy of this many MiB (read + write that much each), "
+                         "the known-traffic dispatch that hardware-counter readings are scaled by")
     return ap.parse_args()
 
 
@@ -175,7 +186,8 @@ def main():
         call, mult = kernels[kname]
         tf = mult * pair_flops / (parts[call] * 1e-3) / 1e12
         return {"kernel": kname, "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": tf / PEAK_BF16_TFLOPS, "traffic": None, "avg_launch_ms": parts[call],
+                "frac": tf / PEAK_BF16_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, kname)) if not over else None, "avg_launch_ms": parts[call],
                 "algorithmic_flops_per_launch": mult * pair_flops}
 
     out = {
@@ -208,6 +220,12 @@ def main():
         out["dense_baseline"] = {"fwd_ms": td_f, "bwd_ms": td_b, "ms": td_f + td_b,
                                  "tflops": dense_flops / ((td_f + td_b) * 1e-3) / 1e12,
                                  "speedup_of_bsa": (td_f + td_b) / ms_step}
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib * (1 << 18), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)  # one vectorized elementwise dispatch: reads and writes calibration_copy_mib MiB
+        torch.cuda.synchronize()
+        out["calibration_copy_mib"] = args.calibration_copy_mib
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, max(1, min(args.cpu_heads, wl.H)))
     print(json.dumps(out))
