@@ -134,6 +134,7 @@ def main():
     O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
     LSE = torch.empty((wl.B, wl.H, wl.L), dtype=torch.float32, device=dev)
     ws = torch.empty(max(1, B.bwd_workspace_bytes(shp, nk)), dtype=torch.uint8, device=dev)
+    fws = torch.empty(max(1, B.fwd_workspace_bytes(shp, nk)), dtype=torch.uint8, device=dev)
 
     def indices():
         B.pool_blocks(shp, Q, Qbar)
@@ -142,7 +143,7 @@ def main():
         B.prune_q(shp, Q, wl.keep_ratio, keep)
 
     def fwd():
-        B.attn_fwd(shp, Q, K, V, lists, keep, O=O, LSE=LSE)
+        B.attn_fwd(shp, Q, K, V, lists, keep, O=O, LSE=LSE, workspace=fws)
 
     def bwd(stages=None):
         B.attn_bwd(shp, Q, K, V, O, LSE, dO, lists, keep, dQ=dQ, dK=dK, dV=dV, workspace=ws, stages=stages)

@@ -110,11 +110,16 @@ int bsa_prune_q(const bsa_shape_t* shape, const void* Q, double keep_ratio,
  *   O   out [B,H,L,d] shape.dtype,  LSE out [B,H,L] float (natural-log sum-exp, filled too)
  * Every row must list at least one KV block (Eq. 4 always selects one).
  * keep_idx rows must be ascending, distinct, in [0,Bk) and contain the center.
+ *   workspace   bsa_fwd_workspace_bytes(shape, n_keep) bytes of device scratch (may be NULL
+ *               when that is 0), else BSA_ERR_WORKSPACE.  It holds the partial results of
+ *               the query blocks whose KV walk is split over several workgroups to balance a
+ *               short launch; contents are undefined afterwards.
  */
+size_t bsa_fwd_workspace_bytes(const bsa_shape_t* shape, int n_keep);
 int bsa_attn_fwd(const bsa_shape_t* shape, const void* Q, const void* K, const void* V,
                  const int32_t* q2k_ptr, const int32_t* q2k_idx,
                  const int32_t* keep_idx, int n_keep, float sm_scale,
-                 void* O, float* LSE, void* stream);
+                 void* O, float* LSE, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Backward of bsa_attn_fwd with the index sets held constant (Sec. 3.3: the backward

@@ -21,7 +21,7 @@ _LIB_PATH = os.environ.get("BSA_LIB") or os.path.join(os.path.dirname(os.path.ab
 F32, BF16 = 0, 1
 EXPORTS = (
     "bsa_strerror", "bsa_n_keep", "bsa_pool_blocks", "bsa_select_workspace_bytes", "bsa_select_kv",
-    "bsa_prune_q", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd", "bsa_attn_bwd_stages",
+    "bsa_prune_q", "bsa_fwd_workspace_bytes", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd", "bsa_attn_bwd_stages",
     "bsa_dense_bwd_workspace_bytes", "bsa_dense_attn_fwd", "bsa_dense_attn_bwd",
 )
 
@@ -56,7 +56,8 @@ def lib() -> C.CDLL:
         L.bsa_select_kv.argtypes = [P, vp, vp, f64, f64, vp, vp, i64, vp, vp, vp, vp, sz, vp]
         L.bsa_prune_q.restype, L.bsa_prune_q.argtypes = C.c_int, [P, vp, f64, vp, vp]
         L.bsa_attn_fwd.restype = C.c_int
-        L.bsa_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp]
+        L.bsa_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp]
+        L.bsa_fwd_workspace_bytes.restype, L.bsa_fwd_workspace_bytes.argtypes = sz, [P, i32]
         L.bsa_bwd_workspace_bytes.restype, L.bsa_bwd_workspace_bytes.argtypes = sz, [P, i32]
         L.bsa_attn_bwd.restype = C.c_int
         L.bsa_attn_bwd.argtypes = [P] + [vp] * 11 + [i32, f32, vp, vp, vp, vp, sz, vp]
@@ -185,8 +186,16 @@ def prune_q(shape: Shape, Q: torch.Tensor, keep_ratio: float, out: Optional[torc
     return out
 
 
+def fwd_workspace_bytes(shape: Shape, n_keep_: int) -> int:
+    return lib().bsa_fwd_workspace_bytes(C.byref(shape.c()), n_keep_)
+
+
 def attn_fwd(shape: Shape, Q, K, V, lists: KvLists, keep_idx: torch.Tensor, sm_scale: Optional[float] = None,
-             O: Optional[torch.Tensor] = None, LSE: Optional[torch.Tensor] = None):
+             O: Optional[torch.Tensor] = None, LSE: Optional[torch.Tensor] = None,
+             workspace: Optional[torch.Tensor] = None):
+    nk = keep_idx.shape[-1]
+    if workspace is None:
+        workspace = torch.empty(max(1, fwd_workspace_bytes(shape, nk)), dtype=torch.uint8, device=Q.device)
     if sm_scale is None:
         sm_scale = 1.0 / sqrt(shape.d)
     if O is None:
@@ -194,7 +203,8 @@ def attn_fwd(shape: Shape, Q, K, V, lists: KvLists, keep_idx: torch.Tensor, sm_s
     if LSE is None:
         LSE = torch.empty((shape.B, shape.H, shape.L), dtype=torch.float32, device=Q.device)
     st = lib().bsa_attn_fwd(C.byref(shape.c()), _ptr(Q), _ptr(K), _ptr(V), _ptr(lists.q2k_ptr), _ptr(lists.q2k_idx),
-                            _ptr(keep_idx), keep_idx.shape[-1], sm_scale, _ptr(O), _ptr(LSE), _stream())
+                            _ptr(keep_idx), nk, sm_scale, _ptr(O), _ptr(LSE), _ptr(workspace), workspace.numel(),
+                            _stream())
     _check(st, "bsa_attn_fwd")
     return O, LSE
 

@@ -111,15 +111,26 @@ int bsa_prune_q(const bsa_shape_t* shape, const void* Q, double keep_ratio, int3
   return launch_prune(g, shape->dtype, Q, nk, keep_idx, (hipStream_t)stream);
 }
 
+size_t bsa_fwd_workspace_bytes(const bsa_shape_t* shape, int n_keep) {
+  Geom g;
+  if (make_geom(shape, &g)) return 0;
+  if (n_keep < 1 || n_keep > g.Bk) return 0;
+  return mfma_supported(g, shape->dtype, n_keep) ? fwd_workspace_pipe(g, n_keep) : 0;
+}
+
 int bsa_attn_fwd(const bsa_shape_t* shape, const void* Q, const void* K, const void* V,
                  const int32_t* q2k_ptr, const int32_t* q2k_idx, const int32_t* keep_idx,
-                 int n_keep, float sm_scale, void* O, float* LSE, void* stream) {
+                 int n_keep, float sm_scale, void* O, float* LSE, void* workspace,
+                 size_t workspace_bytes, void* stream) {
   Geom g;
   int rc = make_geom(shape, &g);
   if (rc) return rc;
   if (!Q || !K || !V || !q2k_ptr || !q2k_idx || !keep_idx || !O || !LSE) return BSA_ERR_NULL;
   if (n_keep < 1 || n_keep > g.Bk || !(sm_scale > 0.f) || !std::isfinite(sm_scale)) return BSA_ERR_RANGE;
+  const size_t need = bsa_fwd_workspace_bytes(shape, n_keep);
+  if (need && (!workspace || workspace_bytes < need)) return BSA_ERR_WORKSPACE;
   AttnArgs a{};
+  a.fwd_ws = need ? workspace : nullptr;
   a.Q = Q; a.K = K; a.V = V; a.q2k_ptr = q2k_ptr; a.q2k_idx = q2k_idx; a.keep_idx = keep_idx;
   a.n_keep = n_keep; a.sm_scale = sm_scale; a.O_out = O; a.LSE_out = LSE;
   if (mfma_supported(g, shape->dtype, n_keep)) return launch_fwd_pipe(g, a, (hipStream_t)stream);

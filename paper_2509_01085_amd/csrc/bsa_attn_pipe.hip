@@ -33,33 +33,130 @@ __device__ inline int xcd_remap8(int n, int total) {
   return x * q + min(x, r) + (n >> 3);
 }
 
+// ---- work items -------------------------------------------------------------------------
+// A launch covers `units` units of work (four query blocks of a head each).  Workgroups are
+// dispatched round-robin over the 8 XCDs, so XCD x is given the contiguous unit range
+// [x*q + min(x, r), ...) with q = units / 8, r = units % 8: neighbouring query blocks, whose
+// lists overlap, share that XCD's L2.  When the launch is only a few rounds long (units per
+// workgroup slot), its tail leaves most of the chip idle; then the last split_n units of every
+// XCD's range are walked in split_S segments by separate, shorter workgroups dispatched last,
+// and a combine launch merges their partial results.
+constexpr int kCUs = 256;  // compute units of the MI355X
+
+#ifdef BSA_TRACE  // development aid: per-workgroup start/end times of the forward launch
+__device__ unsigned long long g_trace[4 * 65536];
+#define BSA_TRACE_BEGIN() const unsigned long long trace_t0 = wall_clock64()
+#define BSA_TRACE_END()                                                                       \
+  if (threadIdx.x == 0 && blockIdx.x < 65536) {                                               \
+    g_trace[4 * blockIdx.x] = trace_t0;                                                       \
+    g_trace[4 * blockIdx.x + 1] = wall_clock64();                                             \
+    g_trace[4 * blockIdx.x + 2] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));       \
+    g_trace[4 * blockIdx.x + 3] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));      \
+  }
+#else
+#define BSA_TRACE_BEGIN()
+#define BSA_TRACE_END()
+#endif
+
+struct SplitPlan {
+  int S, n;   // segments per split unit; split units per XCD (0: no splitting)
+  int grid;   // workgroups of the main launch
+  int units;  // number of split units = workgroups of the combine launch
+};
+
+static SplitPlan plan_split(int units, int slots, bool allow) {
+  SplitPlan p{1, 0, 0, 0};
+  const int q = units / 8, r = units % 8, cmax = q + (r ? 1 : 0);
+  if (allow && q >= 5 && units < 12 * slots) {  // short launch: split the last fifth in four
+    p.S = 4;
+    p.n = (q + 4) / 5;
+  }
+  p.grid = 8 * (cmax - p.n + p.S * p.n);
+  p.units = 8 * p.n;
+  return p;
+}
+
+struct Item {
+  int unit, seg, nseg;
+  int sidx;  // ordinal of a split unit (addresses its partial results), -1 for a whole unit
+};
+
+__device__ inline bool item_of(int b, int units, int S, int n, Item& it) {
+  const int q = units >> 3, r = units & 7, x = b & 7, k = b >> 3;
+  const int start = x * q + min(x, r), cnt = q + (x < r ? 1 : 0), whole = cnt - n;
+  if (k < whole) {
+    it.unit = start + k; it.seg = 0; it.nseg = 1; it.sidx = -1;
+    return true;
+  }
+  const int kk = k - whole, si = kk / S;
+  if (si >= n) return false;
+  it.unit = start + whole + si; it.seg = kk - si * S; it.nseg = S; it.sidx = x * n + si;
+  return true;
+}
+
+// the split unit a workgroup of the combine launch finishes
+__device__ inline Item split_item_of(int b, int units, int S, int n) {
+  const int q = units >> 3, r = units & 7, x = b & 7, si = b >> 3;
+  Item it;
+  it.unit = x * q + min(x, r) + (q + (x < r ? 1 : 0) - n) + si; it.seg = 0; it.nseg = S; it.sidx = x * n + si;
+  return it;
+}
+
 // Ascending walk over the union of four block lists kept as bit masks in LDS.  Every value
 // is wave-uniform; readfirstlane moves the words to scalar registers so the bit scanning
 // costs scalar, not vector, instructions.
 struct Walk4 {
   const uint32_t* masks;  // [4][W]
-  int W, own_list, word;
+  int W, own_list, word, left;
   uint32_t u, own;
-  __device__ inline Walk4(const uint32_t* m, int W_, int own_) : masks(m), W(W_), own_list(own_), word(-1), u(0), own(0) {}
+  __device__ inline Walk4(const uint32_t* m, int W_, int own_)
+      : masks(m), W(W_), own_list(own_), word(-1), left(0x7fffffff), u(0), own(0) {}
+  __device__ inline void load() {
+    const uint32_t all = masks[word] | masks[W + word] | masks[2 * W + word] | masks[3 * W + word];
+    u = __builtin_amdgcn_readfirstlane(all);
+    own = __builtin_amdgcn_readfirstlane(masks[own_list * W + word]);
+  }
   __device__ inline int next(bool& mine) {
+    if (left <= 0) return -1;
     while (u == 0) {
       if (++word >= W) return -1;
-      const uint32_t all = masks[word] | masks[W + word] | masks[2 * W + word] | masks[3 * W + word];
-      u = __builtin_amdgcn_readfirstlane(all);
-      own = __builtin_amdgcn_readfirstlane(masks[own_list * W + word]);
+      load();
     }
     const int b = __builtin_ctz(u);
     u &= u - 1;
     mine = (own >> b) & 1u;
+    --left;
     return word * 32 + b;
+  }
+  // restrict a fresh walk to segment `seg` of `nseg` equal parts of the union
+  __device__ inline void restrict_to(int seg, int nseg) {
+    int total = 0;
+    for (int w = 0; w < W; ++w) {
+      const uint32_t all = masks[w] | masks[W + w] | masks[2 * W + w] | masks[3 * W + w];
+      total += __builtin_popcount(__builtin_amdgcn_readfirstlane(all));
+    }
+    int skip = (int)((int64_t)seg * total / nseg);
+    left = (int)((int64_t)(seg + 1) * total / nseg) - skip;
+    while (++word < W) {
+      load();
+      const int c = __builtin_popcount(u);
+      if (skip < c) break;
+      skip -= c;
+      u = 0;
+    }
+    for (; skip > 0; --skip) u &= u - 1;
   }
 };
 
 #define BSA_FENCE() __builtin_amdgcn_sched_barrier(0)
 #define BSA_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
 
-template <int D, bool SPLITQ>
+// COMBINE = false: the walk (a whole unit, or one segment of a split unit, whose unnormalised
+// accumulators, running maxima and sums go to a.part).  COMBINE = true: merge the segments of
+// a split unit and finish it.  Both end in the same epilogue.
+template <int D, bool SPLITQ, bool COMBINE>
 __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g, AttnArgs a) {
+  BSA_TRACE_BEGIN();
   constexpr int NT = SPLITQ ? 512 : 256;  // threads
   constexpr int NB = SPLITQ ? 4 : 2;      // LDS ring depth (tiles)
   constexpr int RB = D * 2;               // bytes per tile row
@@ -78,8 +175,13 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = lane >> 5, col = lane & 31;
   const int qb = wave & 3, sub = wave >> 2;  // sub: which 32 queries of the block (always 0 with four wavefronts)
+  constexpr int NW = NT / 64;              // wavefronts
+  constexpr int NREG = (D / 32) * 16 + 2;  // floats per lane of a partial result: O^T tile, m, l
   const int ngroups = (g.N + PG - 1) / PG;
-  const int unit = xcd_remap8(blockIdx.x, gridDim.x);
+  Item it;
+  if (COMBINE) it = split_item_of(blockIdx.x, ngroups * g.B * g.H, a.split_S, a.split_n);
+  else if (!item_of(blockIdx.x, ngroups * g.B * g.H, a.split_S, a.split_n, it)) return;
+  const int unit = it.unit;
   const int64_t bh = unit / ngroups;
   const int i = (unit % ngroups) * PG + qb;  // this wavefront's query block
   const bool valid = i < g.N;
@@ -92,10 +194,11 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
   float* Lh = a.LSE_out + bh * g.L;
 
   if (tid < PBK) koff[tid] = intra_offset(g, tid);
-  for (int k = tid; k < PG * W; k += NT) masks[k] = 0u;
+  if (!COMBINE)
+    for (int k = tid; k < PG * W; k += NT) masks[k] = 0u;
   if (tid < 2 * PG) keepbits[tid >> 1][tid & 1] = 0u;
   __syncthreads();
-  if (valid && sub == 0) {
+  if (!COMBINE && valid && sub == 0) {
     if (g.dense) {
       for (int w = lane; w < W; w += 64)
         masks[qb * W + w] = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
@@ -137,7 +240,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
 #pragma unroll
   for (int s = 0; s < DS; ++s) {
     u32x4 v = {0u, 0u, 0u, 0u};
-    if (qid >= 0) v = *reinterpret_cast<const u32x4*>(Qh + (int64_t)qtok * D + 16 * s + 8 * grp);
+    if (!COMBINE && qid >= 0) v = *reinterpret_cast<const u32x4*>(Qh + (int64_t)qtok * D + 16 * s + 8 * grp);
     qf[s] = as_frag(v);
   }
 #pragma unroll
@@ -167,10 +270,27 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
   const float c2 = a.sm_scale * kLog2e;
   __syncthreads();
 
+  // partial results of split unit sidx: [segment][wavefront][NREG][64 lanes] floats
+  float* part = it.sidx >= 0 ? a.part + ((int64_t)it.sidx * a.split_S * NW + wave) * (NREG * 64) + lane : nullptr;
+  if (COMBINE) {
+    // merge the segments in order: m = max m_s, (l, O~) = sum of (l_s, O~_s) 2^(m_s - m)
+    for (int sg = 0; sg < it.nseg; ++sg) m = fmaxf(m, part[(int64_t)sg * NW * NREG * 64 + (NREG - 2) * 64]);
+    for (int sg = 0; sg < it.nseg; ++sg) {
+      const float* ps = part + (int64_t)sg * NW * NREG * 64;
+      const float ms = ps[(NREG - 2) * 64];
+      const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - m);
+      l += w * ps[(NREG - 1) * 64];
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] += w * ps[(dt * 16 + r) * 64];
+    }
+  }
   Walk4 walk(masks, W, qb);  // runs NB-1 tiles ahead of the multiplication; `pending` remembers
   int issued = 0;            // for the tiles in flight whether this wavefront's list has them
   uint32_t pending = 0;
-  {
+  if (!COMBINE) {
+    if (it.nseg > 1) walk.restrict_to(it.seg, it.nseg);
 #pragma unroll
     for (int k = 0; k < NB - 1; ++k) {
       bool mk = false;
@@ -272,6 +392,17 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
     }
   }
 
+  if (!COMBINE && it.nseg > 1) {  // a segment: leave the partial result, the combine launch finishes the unit
+    float* ps = part + (int64_t)it.seg * NW * NREG * 64;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) ps[(dt * 16 + r) * 64] = o[dt][r];
+    ps[(NREG - 2) * 64] = m;
+    ps[(NREG - 1) * 64] = l;
+    BSA_TRACE_END();
+    return;
+  }
   // epilogue: normalise, store the retained rows, park the center's row for the fill
   const float ltot = l + xor32(l);
   const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
@@ -306,6 +437,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
       Lh[tok] = cen_lse[qb];
     }
   }
+  if (!COMBINE) { BSA_TRACE_END(); }
 }
 
 // =====================================================================================
@@ -423,7 +555,8 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------- dQ
-template <int D, bool SPLITQ>
+// COMBINE as in the forward: segments of a split unit leave their dQ^T sums in a.part.
+template <int D, bool SPLITQ, bool COMBINE>
 __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom g, AttnArgs a) {
   using R = BwdRec<D, SPLITQ ? 2 : 1>;
   constexpr int NT = SPLITQ ? 512 : 256;
@@ -439,8 +572,13 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = lane >> 5, col = lane & 31;
   const int qb = wave & 3, sub = wave >> 2;
+  constexpr int NW = NT / 64;          // wavefronts
+  constexpr int NREG = (D / 32) * 16;  // floats per lane of a partial result: the dQ^T tile
   const int ngroups = (g.N + PG - 1) / PG;
-  const int unit = xcd_remap8(blockIdx.x, gridDim.x);
+  Item it;
+  if (COMBINE) it = split_item_of(blockIdx.x, ngroups * g.B * g.H, a.split_S, a.split_n);
+  else if (!item_of(blockIdx.x, ngroups * g.B * g.H, a.split_S, a.split_n, it)) return;
+  const int unit = it.unit;
   const int64_t bh = unit / ngroups;
   const int i = (unit % ngroups) * PG + qb;
   const bool valid = i < g.N;
@@ -452,10 +590,11 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
   const uint8_t* rec = static_cast<const uint8_t*>(a.ws) + row * (int64_t)R::BYTES;
 
   if (tid < PBK) koff[tid] = intra_offset(g, tid);
-  for (int k = tid; k < PG * W; k += NT) masks[k] = 0u;
+  if (!COMBINE)
+    for (int k = tid; k < PG * W; k += NT) masks[k] = 0u;
   if (tid < 2 * PG) keepbits[tid >> 1][tid & 1] = 0u;
   __syncthreads();
-  if (valid && sub == 0) {
+  if (!COMBINE && valid && sub == 0) {
     if (g.dense) {
       for (int w = lane; w < W; w += 64)
         masks[qb * W + w] = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
@@ -497,7 +636,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
 #pragma unroll
   for (int s = 0; s < DS; ++s) {
     u32x4 qv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
-    if (qid >= 0) {
+    if (!COMBINE && qid >= 0) {
       const int off = qpos * RB + (((2 * s + grp) ^ swz<D>(qpos)) << 4);
       qv = *reinterpret_cast<const u32x4*>(rec + R::QC + off);
       gv = *reinterpret_cast<const u32x4*>(rec + R::GC + off);
@@ -533,10 +672,22 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
   const float c2 = a.sm_scale * kLog2e;
   __syncthreads();
 
+  // partial results of split unit sidx: [segment][wavefront][NREG][64 lanes] floats
+  float* part = it.sidx >= 0 ? a.part + ((int64_t)it.sidx * a.split_S * NW + wave) * (NREG * 64) + lane : nullptr;
+  if (COMBINE) {
+    for (int sg = 0; sg < it.nseg; ++sg) {
+      const float* ps = part + (int64_t)sg * NW * NREG * 64;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dq[dt][r] += ps[(dt * 16 + r) * 64];
+    }
+  }
   Walk4 walk(masks, W, qb);
   int issued = 0;
   uint32_t pending = 0;
-  {
+  if (!COMBINE) {
+    if (it.nseg > 1) walk.restrict_to(it.seg, it.nseg);
 #pragma unroll
     for (int k = 0; k < NB - 1; ++k) {
       bool mk = false;
@@ -617,6 +768,14 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
     }
   }
 
+  if (!COMBINE && it.nseg > 1) {
+    float* ps = part + (int64_t)it.seg * NW * NREG * 64;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) ps[(dt * 16 + r) * 64] = dq[dt][r];
+    return;
+  }
   if (qid >= 0) {
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -914,22 +1073,37 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
   }
 }
 
+// floats per lane of one wavefront's partial result
+constexpr int fwd_part_regs(int d) { return (d / 32) * 16 + 2; }
+constexpr int dq_part_regs(int d) { return (d / 32) * 16; }
+
+static SplitPlan fwd_plan(const Geom& g, int n_keep, bool allow) {
+  const bool splitq = n_keep > 32;
+  return plan_split(((g.N + PG - 1) / PG) * g.B * g.H, kCUs * (splitq ? 1 : 2), allow);
+}
+
 template <int D, int NQT>
-static int launch_bwd_pipe_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
+static int launch_bwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
   using R = BwdRec<D, NQT>;
   constexpr bool SPLITQ = NQT == 2;
   const int W = (g.N + 31) / 32;
   if (a.stages & BSA_BWD_PRE) hipLaunchKernelGGL((bwd_pre_pipe_kernel<D, NQT>), dim3(g.rows), dim3(256), 0, st, g, a);
   const size_t lds_q = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PG * W * 4;
   const size_t lds_kv = (size_t)4 * PBK * D * 2 + (size_t)DkvRing<NQT>::NB * R::BYTES + (size_t)2 * W * 4;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_pipe_kernel<D, SPLITQ>),
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_pipe_kernel<D, SPLITQ, false>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q) != hipSuccess ||
       hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_pipe_kernel<D, NQT>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv) != hipSuccess)
     return BSA_ERR_LAUNCH;
-  if (a.stages & BSA_BWD_DQ)
-    hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ>), dim3(((g.N + PG - 1) / PG) * g.B * g.H), dim3(SPLITQ ? 512 : 256),
-                       lds_q, st, g, a);
+  if (a.stages & BSA_BWD_DQ) {
+    const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense);  // the dQ walk is the forward's walk
+    a.split_S = p.S;
+    a.split_n = p.n;
+    a.part = reinterpret_cast<float*>(static_cast<uint8_t*>(a.ws) + (size_t)R::BYTES * g.rows);  // behind the records
+    hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ, false>), dim3(p.grid), dim3(SPLITQ ? 512 : 256), lds_q, st, g, a);
+    if (p.units)
+      hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ, true>), dim3(p.units), dim3(SPLITQ ? 512 : 256), 0, st, g, a);
+  }
   if (a.stages & BSA_BWD_DKV)
     hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D, NQT>), dim3(((g.N + 1) / 2) * g.B * g.H), dim3(512), lds_kv, st, g, a);
   return check_launch();
@@ -945,17 +1119,31 @@ size_t bwd_workspace_pipe(const Geom& g, int n_keep) {
   const bool two = n_keep > 32;
   const size_t per_row = g.d == 128 ? (two ? BwdRec<128, 2>::BYTES : BwdRec<128, 1>::BYTES)
                                     : (two ? BwdRec<64, 2>::BYTES : BwdRec<64, 1>::BYTES);
-  return per_row * (size_t)g.rows;
+  const SplitPlan p = fwd_plan(g, n_keep, !g.dense);
+  const size_t partials = (size_t)p.units * p.S * (two ? 8 : 4) * dq_part_regs(g.d) * 64 * sizeof(float);
+  return per_row * (size_t)g.rows + partials;
+}
+
+size_t fwd_workspace_pipe(const Geom& g, int n_keep) {
+  if (g.dense) return 0;
+  const SplitPlan p = fwd_plan(g, n_keep, true);
+  return (size_t)p.units * p.S * (n_keep > 32 ? 8 : 4) * fwd_part_regs(g.d) * 64 * sizeof(float);
 }
 
 template <int D, bool SPLITQ>
-static int launch_fwd_pipe_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
+static int launch_fwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
   const int W = (g.N + 31) / 32;
   const size_t lds = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PG * W * 4;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ>),
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ, false>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
     return BSA_ERR_LAUNCH;
-  hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ>), dim3(((g.N + PG - 1) / PG) * g.B * g.H), dim3(SPLITQ ? 512 : 256), lds, st, g, a);
+  const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense && a.fwd_ws != nullptr);
+  a.split_S = p.S;
+  a.split_n = p.n;
+  a.part = static_cast<float*>(a.fwd_ws);
+  hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ, false>), dim3(p.grid), dim3(SPLITQ ? 512 : 256), lds, st, g, a);
+  if (p.units)
+    hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ, true>), dim3(p.units), dim3(SPLITQ ? 512 : 256), 0, st, g, a);
   return check_launch();
 }
 
@@ -966,3 +1154,9 @@ int launch_fwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st) {
 }
 
 }  // namespace bsa
+
+#ifdef BSA_TRACE
+extern "C" int bsa_debug_trace(void* host_dst, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(bsa::g_trace), bytes);
+}
+#endif

@@ -93,6 +93,12 @@ struct AttnArgs {
   float* LSE_out;
   void* ws;
   unsigned stages;  // backward only: which of its kernels to launch (bsa_bwd_stage bits)
+  // tail splitting (MFMA path): on every XCD the last split_n units of a launch are walked in
+  // split_S segments by separate workgroups, which leave fp32 partial results in `part` for a
+  // combine launch; split_n == 0 turns it off.  fwd_ws: the forward's own workspace.
+  int split_S, split_n;
+  float* part;
+  void* fwd_ws;
 };
 
 // plain-ALU fp32-accumulate kernels: any supported shape, fp32 or bf16 storage
@@ -105,5 +111,6 @@ bool mfma_supported(const Geom& g, int dtype, int n_keep);  // shapes the bf16 M
 int launch_fwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st);
 int launch_bwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st);
 size_t bwd_workspace_pipe(const Geom& g, int n_keep);
+size_t fwd_workspace_pipe(const Geom& g, int n_keep);
 
 }  // namespace bsa

@@ -72,9 +72,16 @@ def test_null_range_capacity_workspace_errors_come_before_any_launch():
     assert sel(cap=rows_n - 1) == -4
     assert sel(ws=None) == -7 and sel(wsb=ws - 1) == -7
     assert sel(kp=None) == -1  # k2q pointers: both or neither
-    assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 0, 0.125, p, p, None) == -3
-    assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 33, 0.125, p, p, None) == -3
-    assert lib.bsa_attn_fwd(s, p, p, None, p, p, p, 16, 0.125, p, p, None) == -1
+    assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 0, 0.125, p, p, None, 0, None) == -3
+    assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 33, 0.125, p, p, None, 0, None) == -3
+    assert lib.bsa_attn_fwd(s, p, p, None, p, p, p, 16, 0.125, p, p, None, 0, None) == -1
+    assert B.fwd_workspace_bytes(GOOD, 16) == 0  # fp32 shapes run the plain kernels: nothing to split
+    big = B.Shape(1, 12, 20, 32, 52, 4, 4, 4, 128, B.BF16)  # a short launch on the MFMA path: the tail is split
+    fws = B.fwd_workspace_bytes(big, 32)
+    assert fws > 0 and B.bwd_workspace_bytes(big, 32) > big.rows * 16640
+    sb = C.byref(big.c())
+    assert lib.bsa_attn_fwd(sb, p, p, p, p, p, p, 32, 0.125, p, p, None, fws, None) == -7
+    assert lib.bsa_attn_fwd(sb, p, p, p, p, p, p, 32, 0.125, p, p, p, fws - 1, None) == -7
     wsb = B.bwd_workspace_bytes(GOOD, 16)
     assert wsb > 0 and B.bwd_workspace_bytes(GOOD, 0) == 0
     bwd = lambda ws, wsbytes, nk=16: lib.bsa_attn_bwd(s, *([p] * 11), nk, 0.125, p, p, p, ws, wsbytes, None)

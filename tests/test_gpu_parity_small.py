@@ -36,6 +36,11 @@ CASES = {
     "keep_one": Workload("keep_one", 1, 2, 64, "fp32", (4, 8, 8), (2, 4, 4), threshold=0.6, keep_ratio=1 / 32),
     # maximum block size and head dimension
     "max_block": Workload("max_block", 1, 1, 256, "fp32", (8, 8, 8), (4, 8, 8), threshold=0.9, keep_ratio=0.3),
+    # short launches on the MFMA path: on each XCD the walks of the last units are split over
+    # several workgroups and merged by a combine launch (48 units; 60 units, not a multiple of 8,
+    # last query-block group ragged, two wavefronts per query block)
+    "split_tail": Workload("split_tail", 1, 2, 128, "bf16", (16, 16, 24), (4, 4, 4), threshold=0.7),
+    "split_ragged": Workload("split_ragged", 1, 5, 64, "bf16", (12, 12, 20), (4, 4, 4), threshold=0.7, keep_ratio=0.75),
     # threshold 1: every block selected
     "p_one": Workload("p_one", 1, 1, 64, "bf16", (4, 8, 8), (2, 4, 4), threshold=1.0, keep_ratio=0.5),
 }
