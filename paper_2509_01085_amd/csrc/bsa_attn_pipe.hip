@@ -470,11 +470,14 @@ struct BwdRec {  // byte layout of one query block's record (workspace image == 
 template <int D, int NQT>
 __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
   using R = BwdRec<D, NQT>;
-  __shared__ float dpart[R::NQ][4];
+  constexpr int CPR = D / 8;       // 16-byte chunks per row
+  constexpr int RPP = 256 / CPR;   // rows covered by one pass of the workgroup (a row = CPR adjacent lanes)
+  __shared__ __align__(16) float fold[RPP][D];  // column sums of the pruned tokens' dO, per row group
   __shared__ int keepflag[PBK];
   __shared__ int qtok[R::NQ];
   __shared__ int koff[PBK];
   const int tid = threadIdx.x;
+  const int c = tid % CPR, rg = tid / CPR;
   const int64_t row = blockIdx.x;
   const int64_t bh = row / g.N;
   const int i = row % g.N;
@@ -491,10 +494,10 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
   }
   __syncthreads();
   if (tid < R::NQ) {
-    int c = -1;
-    if (tid < a.n_keep) c = g.dense ? tid : min(max(a.keep_idx[row * a.n_keep + tid], 0), PBK - 1);
-    qtok[tid] = c >= 0 ? origin + koff[c] : -1;
-    if (c >= 0) keepflag[c] = 1;
+    int k = -1;
+    if (tid < a.n_keep) k = g.dense ? tid : min(max(a.keep_idx[row * a.n_keep + tid], 0), PBK - 1);
+    qtok[tid] = k >= 0 ? origin + koff[k] : -1;
+    if (k >= 0) keepflag[k] = 1;
   }
   __syncthreads();
   int cpos = -1;  // position of the center among the retained rows (same in every thread)
@@ -502,55 +505,62 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
     for (int q = 0; q < a.n_keep; ++q)
       if (qtok[q] == origin + koff[g.center]) cpos = q;
 
-  // thread (q = tid / 4 + 64 * pass, part = tid % 4) handles D/4 channels of row q
-  constexpr int CH = D / 4;
-  for (int q = tid >> 2; q < R::NQ; q += 64) {
-    const int part = tid & 3;
-    const int tok = qtok[q];
-    float dsum = 0.f;
-    for (int c8 = 0; c8 < CH; c8 += 8) {
-      const int ch = part * CH + c8;
-      u32x4 qv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
-      if (tok >= 0) {
-        qv = *reinterpret_cast<const u32x4*>(Qh + (int64_t)tok * D + ch);
-        gv = *reinterpret_cast<const u32x4*>(dOh + (int64_t)tok * D + ch);
-        const u32x4 ov = *reinterpret_cast<const u32x4*>(Oh + (int64_t)tok * D + ch);
-        float gf[8];
+  // gradient of the fill copies: the dO rows of the pruned tokens, summed per channel; a
+  // thread adds its row group's tokens in ascending id, the groups are added in order below
+  if (!g.dense) {
+    float acc[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          gf[2 * e] = __uint_as_float(gv[e] << 16);
-          gf[2 * e + 1] = __uint_as_float(gv[e] & 0xffff0000u);
-        }
-        if (q == cpos) {  // fold the fill copies: pruned tokens, ascending intra-block id
-          for (int u = 0; u < PBK; ++u) {
-            if (keepflag[u]) continue;
-            const u32x4 pv = *reinterpret_cast<const u32x4*>(dOh + (int64_t)(origin + koff[u]) * D + ch);
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int u = rg; u < PBK; u += RPP) {
+      if (keepflag[u]) continue;
+      const u32x4 pv = *reinterpret_cast<const u32x4*>(dOh + (int64_t)(origin + koff[u]) * D + 8 * c);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              gf[2 * e] += __uint_as_float(pv[e] << 16);
-              gf[2 * e + 1] += __uint_as_float(pv[e] & 0xffff0000u);
-            }
-          }
-#pragma unroll
-          for (int e = 0; e < 4; ++e) gv[e] = pack_bf16(gf[2 * e], gf[2 * e + 1]);
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          dsum += gf[2 * e] * __uint_as_float(ov[e] << 16);
-          dsum += gf[2 * e + 1] * __uint_as_float(ov[e] & 0xffff0000u);
-        }
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] += __uint_as_float(pv[e] << 16);
+        acc[2 * e + 1] += __uint_as_float(pv[e] & 0xffff0000u);
       }
-      const int pos = (ch >> 3) ^ swz<D>(q);  // chunk position inside the swizzled row
-      *reinterpret_cast<u32x4*>(rec + R::QC + q * R::RB + pos * 16) = qv;
-      *reinterpret_cast<u32x4*>(rec + R::GC + q * R::RB + pos * 16) = gv;
     }
-    dpart[q][part] = dsum;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) fold[rg][8 * c + e] = acc[e];
   }
   __syncthreads();
-  if (tid < R::NQ) {
-    const int tok = qtok[tid];
-    reinterpret_cast<float*>(rec + R::LS)[tid] = tok >= 0 ? Lh[tok] * kLog2e : INFINITY;  // padding rows: exp2(x - inf) = 0
-    reinterpret_cast<float*>(rec + R::DL)[tid] = tok >= 0 ? (dpart[tid][0] + dpart[tid][1]) + (dpart[tid][2] + dpart[tid][3]) : 0.f;
+
+  for (int q = rg; q < R::NQ; q += RPP) {
+    const int tok = qtok[q];
+    u32x4 qv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
+    float dsum = 0.f;
+    if (tok >= 0) {
+      qv = *reinterpret_cast<const u32x4*>(Qh + (int64_t)tok * D + 8 * c);
+      gv = *reinterpret_cast<const u32x4*>(dOh + (int64_t)tok * D + 8 * c);
+      const u32x4 ov = *reinterpret_cast<const u32x4*>(Oh + (int64_t)tok * D + 8 * c);
+      float gf[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        gf[2 * e] = __uint_as_float(gv[e] << 16);
+        gf[2 * e + 1] = __uint_as_float(gv[e] & 0xffff0000u);
+      }
+      if (q == cpos) {
+        for (int k = 0; k < RPP; ++k)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) gf[e] += fold[k][8 * c + e];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) gv[e] = pack_bf16(gf[2 * e], gf[2 * e + 1]);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        dsum += gf[2 * e] * __uint_as_float(ov[e] << 16);
+        dsum += gf[2 * e + 1] * __uint_as_float(ov[e] & 0xffff0000u);
+      }
+    }
+    const int pos = c ^ swz<D>(q);  // chunk position inside the swizzled row
+    *reinterpret_cast<u32x4*>(rec + R::QC + q * R::RB + pos * 16) = qv;
+    *reinterpret_cast<u32x4*>(rec + R::GC + q * R::RB + pos * 16) = gv;
+#pragma unroll
+    for (int msk = 1; msk < CPR; msk <<= 1) dsum += __shfl_xor(dsum, msk);  // the row's CPR lanes
+    if (c == 0) {
+      reinterpret_cast<float*>(rec + R::LS)[q] = tok >= 0 ? Lh[tok] * kLog2e : INFINITY;  // padding rows: exp2(x - inf) = 0
+      reinterpret_cast<float*>(rec + R::DL)[q] = dsum;
+    }
   }
 }
 

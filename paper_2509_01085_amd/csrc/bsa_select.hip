@@ -7,9 +7,9 @@
 //   1. scores_kernel       s[r][j] = score_scale * <Qbar_r, Kbar_j>, fp64, channel-ascending,
 //                          multiply and add rounded separately (the order another
 //                          implementation must follow to reproduce every comparison)
-//   2. row_select_kernel   one workgroup per row: bitonic sort in LDS on (s desc, j asc),
-//                          e = exp(s - s_max), scan, k* = 1 + #{c_k < p*Z}; marks the k*
-//                          leading blocks in a bit mask, writes k*
+//   2. row_select_kernel   one workgroup per row: e = exp(s - s_max), Z, then a bisection for
+//                          the key of the last block of the minimal prefix (no sort); marks
+//                          the k* selected blocks in a bit mask, writes k*
 //   3. scan_kernel         exclusive scan of the counts -> q2k_ptr, nnz
 //   4. expand_kernel       bit mask -> ascending block ids at q2k_ptr[r]
 //   5-7. transpose         per (head, 32 columns): ballot-count, scan, ballot-fill -> k2q
@@ -90,79 +90,213 @@ __global__ __launch_bounds__(256) void scores_kernel(Geom g, const double* Qbar,
 }
 
 // ---------------------------------------------------------------- 2. per-row selection
-__device__ inline bool before(double sa, int ja, double sb, int jb) {
-  return sa > sb || (sa == sb && ja < jb);
+// Eq. 4 without a sort.  In the order (score descending, block id ascending) the selected set
+// is a prefix, so it is fixed by the key of its last element.  Scores map to 64-bit integers
+// that order the same way; with G(t) = sum of e_j over keys >= t (non-increasing in t) the
+// last selected key is the largest t with G(t) >= p*Z.  It is found by bisection over the
+// bits of t, keeping the bracket [lo, hi) with G(lo) >= p*Z > G(hi) and the number of keys
+// inside it; the search stops as soon as one key is left (about log2 N steps past the keys'
+// common prefix).  More than one key left after the last bit means equal scores: those are
+// taken in ascending block id while the mass is short.  Sums run in a fixed order (per lane
+// ascending, butterfly across lanes, wavefronts in order), so the result is reproducible;
+// it equals the sequential-prefix definition whenever no comparison is within rounding of a
+// tie, which the callers' margin check establishes.
+__device__ inline unsigned long long order_key(double s) {
+  if (s == 0.0) s = 0.0;  // -0 and +0 compare equal
+  const unsigned long long u = (unsigned long long)__double_as_longlong(s);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
 }
 
-__global__ __launch_bounds__(256) void row_select_kernel(Geom g, const double* S, double p, int P,
-                                                         uint32_t* mask, int32_t* cnt) {
+__device__ inline double wave_sum(double v) {
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) v = __dadd_rn(v, __shfl_xor(v, m));
+  return v;
+}
+
+template <int NW, int MAXE>
+__global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const double* S, double p,
+                                                            uint32_t* mask, int32_t* cnt) {
+  constexpr int NT = 64 * NW;
   extern __shared__ __align__(16) uint8_t smem[];
-  double* key = reinterpret_cast<double*>(smem);        // [P]
-  int* idx = reinterpret_cast<int*>(key + P);           // [P]
-  __shared__ double tot[256];
+  unsigned long long* lkey = reinterpret_cast<unsigned long long*>(smem);  // [N], for the equal-score path
+  __shared__ double red[NW];
+  __shared__ int redc[NW];
   __shared__ uint32_t bits[256];
-  __shared__ int below;
-  const int row = blockIdx.x, tid = threadIdx.x;
+  __shared__ unsigned long long pick;
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const double* s = S + (int64_t)row * g.N;
-  for (int k = tid; k < P; k += 256) {
-    key[k] = k < g.N ? s[k] : -INFINITY;
-    idx[k] = k;
+  const int ept = (g.N + NT - 1) / NT;  // elements per thread actually used (<= MAXE): j = e*NT + tid
+  const int W = (g.N + 31) / 32;
+
+  auto block_sum = [&](double v) -> double {  // the same value in every thread
+    v = wave_sum(v);
+    if (NW == 1) return v;
+    __syncthreads();
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    double t = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) t = __dadd_rn(t, red[w]);
+    return t;
+  };
+  auto block_count = [&](int c) -> int {  // c is wave-uniform
+    if (NW == 1) return c;
+    __syncthreads();
+    if (lane == 0) redc[wave] = c;
+    __syncthreads();
+    int t = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) t += redc[w];
+    return t;
+  };
+
+  double sv[MAXE];
+  double smax = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < MAXE; ++e) {
+    const int j = e * NT + tid;
+    sv[e] = (e < ept && j < g.N) ? s[j] : -INFINITY;
+    smax = fmax(smax, sv[e]);
   }
-  bits[tid] = 0;
-  if (tid == 0) below = 0;
-  __syncthreads();
-  for (int k = 2; k <= P; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int t = tid; t < P / 2; t += 256) {
-        const int lo = (t / j) * 2 * j + (t % j), hi = lo + j;
-        const bool up = (lo & k) == 0;
-        const double sl = key[lo], sh = key[hi];
-        const int jl = idx[lo], jh = idx[hi];
-        const bool hi_first = before(sh, jh, sl, jl);
-        if (hi_first == up) {
-          key[lo] = sh; key[hi] = sl;
-          idx[lo] = jh; idx[hi] = jl;
-        }
-      }
-      __syncthreads();
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) smax = fmax(smax, __shfl_xor(smax, m));
+  if (NW > 1) {
+    if (lane == 0) red[wave] = smax;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) smax = fmax(smax, red[w]);
+  }
+  for (int k = tid; k < 256; k += NT) bits[k] = 0u;
+
+  unsigned long long key[MAXE];
+  double ev[MAXE];
+  double zl = 0.0;
+  unsigned long long kmin = ~0ull, kmax = 0ull;
+#pragma unroll
+  for (int e = 0; e < MAXE; ++e) {
+    const int j = e * NT + tid;
+    const bool live = e < ept && j < g.N;
+    key[e] = live ? order_key(sv[e]) : 0ull;  // padding: below every real key, no mass
+    ev[e] = live ? exp(sv[e] - smax) : 0.0;
+    zl = __dadd_rn(zl, ev[e]);
+    if (live) {
+      lkey[j] = key[e];
+      kmin = key[e] < kmin ? key[e] : kmin;
+      kmax = key[e] > kmax ? key[e] : kmax;
     }
   }
-  // masses relative to the row maximum, in sorted order; padding carries no mass
-  const double smax = key[0];
-  __syncthreads();
-  const int seg = P / 256 > 0 ? P / 256 : 1;  // P is a power of two >= 256
-  const int k0 = tid * seg;
-  double run = 0.0;
-  for (int k = k0; k < k0 + seg; ++k) {
-    const double e = k < g.N ? exp(key[k] - smax) : 0.0;
-    run = __dadd_rn(run, e);
-    key[k] = run;  // inclusive sum inside the segment
-  }
-  tot[tid] = run;
-  __syncthreads();
-  double off = 0.0, Z = 0.0;
-  for (int u = 0; u < 256; ++u) {
-    const double v = tot[u];
-    if (u < tid) off = __dadd_rn(off, v);
-    Z = __dadd_rn(Z, v);
-  }
+  const double Z = block_sum(zl);
   int kstar = g.N;
+  bool all = true;
   if (p < 1.0) {
+    all = false;
     const double target = __dmul_rn(p, Z);
-    int mine = 0;
-    for (int k = k0; k < k0 + seg; ++k)
-      if (k < g.N && __dadd_rn(off, key[k]) < target) ++mine;
-    if (mine) atomicAdd(&below, mine);
+    // common prefix of all keys: the bracket starts there
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) {
+      const unsigned long long a = __shfl_xor(kmin, m), b = __shfl_xor(kmax, m);
+      kmin = a < kmin ? a : kmin;
+      kmax = b > kmax ? b : kmax;
+    }
+    if (NW > 1) {
+      __shared__ unsigned long long rk[2][NW];
+      __syncthreads();
+      if (lane == 0) { rk[0][wave] = kmin; rk[1][wave] = kmax; }
+      __syncthreads();
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        kmin = rk[0][w] < kmin ? rk[0][w] : kmin;
+        kmax = rk[1][w] > kmax ? rk[1][w] : kmax;
+      }
+    }
+    const unsigned long long diff = kmin ^ kmax;
+    int b = diff ? 63 - __builtin_clzll(diff) : -1;  // highest bit in which two keys differ
+    unsigned long long lo = b >= 0 ? (kmin >> b >> 1 << 1 << b) : kmin;  // keys' common prefix, lower bits zero
+    int cnt_lo = g.N, cnt_hi = 0;  // keys >= lo; keys >= hi, hi = lo + 2^(b+1) (not representable when b = 63: never needed)
+    for (; b >= 0 && cnt_lo - cnt_hi > 1; --b) {
+      const unsigned long long cand = lo | (1ull << b);
+      double gl = 0.0;
+      int cl = 0;
+#pragma unroll
+      for (int e = 0; e < MAXE; ++e) {
+        if (e < ept) {
+          const bool ge = key[e] >= cand;
+          gl = __dadd_rn(gl, ge ? ev[e] : 0.0);
+          cl += __popcll(__ballot(ge));
+        }
+      }
+      const double G = block_sum(gl);
+      const int c = block_count(cl);
+      if (G >= target) {
+        lo = cand;
+        cnt_lo = c;
+      } else {
+        cnt_hi = c;
+      }
+    }
+    // the keys still inside the bracket are all equal (one key, unless scores tie exactly)
+    const unsigned long long hi_excl_span = b >= 0 ? (1ull << b << 1) : 1ull;  // bracket = [lo, lo + span), span 0 means up to 2^64
+    int need = 1;
+    if (cnt_lo - cnt_hi > 1) {  // equal scores: add them one at a time, as the sorted prefix would
+      double gl = 0.0, el = 0.0;
+#pragma unroll
+      for (int e = 0; e < MAXE; ++e) {
+        if (e < ept) {
+          gl = __dadd_rn(gl, key[e] > lo ? ev[e] : 0.0);
+          if (key[e] == lo) el = ev[e];
+        }
+      }
+      double c = block_sum(gl);
+      // the mass of one tied element (identical in all of them): take the maximum over threads
+#pragma unroll
+      for (int m = 32; m > 0; m >>= 1) el = fmax(el, __shfl_xor(el, m));
+      if (NW > 1) {
+        __syncthreads();
+        if (lane == 0) red[wave] = el;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NW; ++w) el = fmax(el, red[w]);
+      }
+      const int tied = cnt_lo - cnt_hi;
+      need = 0;
+      do {
+        c = __dadd_rn(c, el);
+        ++need;
+      } while (c < target && need < tied);
+    }
+    kstar = cnt_hi + need;
+    // the last selected key: the unique key of the bracket
+    unsigned long long last = 0ull;
+#pragma unroll
+    for (int e = 0; e < MAXE; ++e)
+      if (e < ept && key[e] >= lo && (hi_excl_span == 0ull || key[e] - lo < hi_excl_span) && key[e] > last) last = key[e];
+    if (tid == 0) pick = 0ull;
     __syncthreads();
-    kstar = min(below + 1, g.N);
-  }
-  for (int k = tid; k < kstar; k += 256) {
-    const int j = idx[k];
-    atomicOr(&bits[j >> 5], 1u << (j & 31));
+    if (last) atomicMax(&pick, last);
+    __syncthreads();
+    last = pick;
+    // mark every key above `last`, and the first `need` blocks whose key equals it
+    const bool tie = cnt_lo - cnt_hi > 1;
+#pragma unroll
+    for (int e = 0; e < MAXE; ++e) {
+      const int j = e * NT + tid;
+      if (e < ept && j < g.N && (key[e] > last || (!tie && key[e] == last))) atomicOr(&bits[j >> 5], 1u << (j & 31));
+    }
+    if (tie && tid == 0) {  // equal scores: ascending block id, one thread (rare)
+      int left = need;
+      for (int j = 0; j < g.N && left > 0; ++j)
+        if (lkey[j] == last) {
+          atomicOr(&bits[j >> 5], 1u << (j & 31));
+          --left;
+        }
+    }
   }
   __syncthreads();
-  const int W = (g.N + 31) / 32;
-  if (tid < W) mask[(int64_t)row * W + tid] = bits[tid];
+  for (int w = tid; w < W; w += NT) {
+    uint32_t v = bits[w];
+    if (all) v = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
+    mask[(int64_t)row * W + w] = v;
+  }
   if (tid == 0) cnt[row] = kstar;
 }
 
@@ -259,16 +393,17 @@ int launch_select(const Geom& g, const double* Qbar, const double* Kbar, double 
   const int BH = g.B * g.H;
   hipLaunchKernelGGL(scores_kernel, dim3((g.N + TJ - 1) / TJ, (g.N + TI - 1) / TI, BH), dim3(256), 0, st,
                      g, Qbar, Kbar, score_scale, w.scores);
-  int P = 256;
-  while (P < g.N) P <<= 1;
-  const size_t lds = (size_t)P * (sizeof(double) + sizeof(int));
-  if (lds > 48 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(row_select_kernel),
+  const size_t lds = (size_t)g.N * sizeof(unsigned long long);  // <= 64 KB
+  if (g.N <= 1024)
+    hipLaunchKernelGGL((row_select_kernel<1, 16>), dim3(g.rows), dim3(64), lds, st, g, w.scores, threshold, w.mask, w.cnt);
+  else if (g.N <= 4096)
+    hipLaunchKernelGGL((row_select_kernel<4, 16>), dim3(g.rows), dim3(256), lds, st, g, w.scores, threshold, w.mask, w.cnt);
+  else {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(row_select_kernel<4, 32>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return BSA_ERR_LAUNCH;
+    hipLaunchKernelGGL((row_select_kernel<4, 32>), dim3(g.rows), dim3(256), lds, st, g, w.scores, threshold, w.mask, w.cnt);
   }
-  hipLaunchKernelGGL(row_select_kernel, dim3(g.rows), dim3(256), lds, st, g, w.scores, threshold, P,
-                     w.mask, w.cnt);
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, w.cnt, g.rows, q2k_ptr, nnz_dev);
   hipLaunchKernelGGL(expand_kernel, dim3((g.rows + 3) / 4), dim3(256), 0, st, g, w.mask, q2k_ptr, q2k_idx);
   if (k2q_ptr) {
