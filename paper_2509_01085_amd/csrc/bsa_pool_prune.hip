@@ -1,9 +1,9 @@
 // Streaming kernels of the index-preparation stage: block mean pooling (Sec. 3.2.3) and
 // query pruning by cosine similarity to the block center (Sec. 3.2.2, Eq. 2).
 //
-// Both are one pass over a [B,H,L,d] tensor and are bound by HBM bandwidth: a workgroup
-// owns one 3D block, pulls its Bk token rows (Cw-token runs of contiguous memory) into LDS
-// with 16-byte loads and does the fp64 decision arithmetic from LDS.
+// Both are one pass over a [B,H,L,d] tensor and are bound by HBM bandwidth: a wavefront
+// owns one 3D block (Bk token rows in Cw-token runs of contiguous memory) and does the fp64
+// decision arithmetic on it.
 //
 // Bit-exactness contract with any other implementation of the same definition: sums run
 // in ascending index order (tokens for pooling, channels for dot products) in fp64.  The
@@ -14,130 +14,227 @@
 
 namespace bsa {
 
-constexpr int kThreads = 256;
-constexpr int kChunkBytes = 32 * 1024;  // token rows staged in LDS per pass
+// One wavefront per 3D block in both kernels, no workgroup barriers: many independent
+// wavefronts per CU keep enough loads in flight to stream at HBM rate.
 
-// Stage rows [c0, c0+nc) of block i of head bh into LDS, row stride `ldw` 32-bit words.
+constexpr int kWaves = 4;  // wavefronts (= blocks) per workgroup
+
 template <int ES>
-__device__ inline void stage_rows(const Geom& g, const uint8_t* X, int64_t bh, int i, int c0, int nc,
-                                  uint32_t* tile, int ldw) {
-  const int vec_per_row = g.d * ES / 16;
-  const int64_t row_bytes = (int64_t)g.d * ES;
-  const int origin = block_origin(g, i);
-  for (int v = threadIdx.x; v < nc * vec_per_row; v += kThreads) {
-    const int r = v / vec_per_row, q = v % vec_per_row;
-    const int64_t tok = origin + intra_offset(g, c0 + r);
-    const uint4 val = *reinterpret_cast<const uint4*>(X + (bh * g.L + tok) * row_bytes + 16 * q);
-    uint32_t* dst = tile + r * ldw + 4 * q;
-    dst[0] = val.x; dst[1] = val.y; dst[2] = val.z; dst[3] = val.w;
-  }
+__device__ inline void unpack(uint32_t w, double& lo, double& hi) {  // ES == 2: two bf16 channels of a word
+  lo = (double)__uint_as_float(w << 16);
+  hi = (double)__uint_as_float(w & 0xffff0000u);
 }
 
+// ------------------------------------------------------------------------------ pooling
+// Lane l owns the 32-bit words l, l + 64, ... of a token row (two bf16 channels or one fp32
+// channel each): every load instruction of the wavefront reads one token's row segment,
+// contiguous in memory, and the per-channel sums run over the tokens in ascending
+// intra-block id, in registers.  No LDS.
 template <int ES>
-__device__ inline double elem(const uint32_t* row, int c) {
-  if (ES == 4) return (double)__uint_as_float(row[c]);
-  const uint32_t w = row[c >> 1];
-  return (double)__uint_as_float((c & 1) ? (w & 0xffff0000u) : (w << 16));
-}
-
-template <int ES>
-__global__ __launch_bounds__(kThreads) void pool_kernel(Geom g, const uint8_t* X, double* Xbar) {
-  __shared__ uint32_t tile[kChunkBytes / 4 + 256];
-  const int row = blockIdx.x;  // (b*H + h)*N + i
+__global__ __launch_bounds__(64 * kWaves) void pool_kernel(Geom g, const uint8_t* X, double* Xbar) {
+  constexpr int KW = 256 * 4 / 4 / 64;  // words per lane at the largest row (d = 256 fp32): 4
+  constexpr int TB = 16;                // token rows loaded ahead of the additions
+  __shared__ int koff[256];
+  for (int t = threadIdx.x; t < g.Bk; t += 64 * kWaves) koff[t] = intra_offset(g, t);
+  __syncthreads();  // the only workgroup barrier
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);  // (b*H + h)*N + i
+  if (row >= g.rows) return;
   const int64_t bh = row / g.N;
-  const int i = row % g.N;
-  const int ldw = g.d * ES / 4 + 1;
-  const int chunk = min(g.Bk, kChunkBytes / (g.d * ES));
-  double acc = 0.0;
-  for (int c0 = 0; c0 < g.Bk; c0 += chunk) {
-    const int nc = min(chunk, g.Bk - c0);
-    __syncthreads();
-    stage_rows<ES>(g, X, bh, i, c0, nc, tile, ldw);
-    __syncthreads();
-    if (threadIdx.x < g.d)
-      for (int r = 0; r < nc; ++r) acc = __dadd_rn(acc, elem<ES>(tile + r * ldw, threadIdx.x));
-  }
-  if (threadIdx.x < g.d) Xbar[(int64_t)row * g.d + threadIdx.x] = __ddiv_rn(acc, (double)g.Bk);
-}
-
-template <int ES>
-__global__ __launch_bounds__(kThreads) void prune_kernel(Geom g, const uint8_t* Q, int n_keep,
-                                                        int32_t* keep_idx) {
-  __shared__ uint32_t tile[kChunkBytes / 4 + 256];
-  __shared__ uint32_t center_row[256];
-  __shared__ double cosv[256];
-  __shared__ int kept[256];
-  const int row = blockIdx.x;
-  const int64_t bh = row / g.N;
-  const int i = row % g.N;
-  const int ldw = g.d * ES / 4 + 1;
-  const int chunk = min(g.Bk, kChunkBytes / (g.d * ES));
-
-  stage_rows<ES>(g, Q, bh, i, g.center, 1, center_row, ldw);
-  __syncthreads();
-  double nc2 = 0.0;  // |q_c|^2, same channel order in every thread
-  for (int c = 0; c < g.d; ++c) {
-    const double x = elem<ES>(center_row, c);
-    nc2 = fma(x, x, nc2);
-  }
-  for (int c0 = 0; c0 < g.Bk; c0 += chunk) {
-    const int nc = min(chunk, g.Bk - c0);
-    __syncthreads();
-    stage_rows<ES>(g, Q, bh, i, c0, nc, tile, ldw);
-    __syncthreads();
-    if (threadIdx.x < nc) {
-      const uint32_t* r = tile + threadIdx.x * ldw;
-      double dot = 0.0, na2 = 0.0;
-      for (int c = 0; c < g.d; ++c) {
-        const double x = elem<ES>(r, c);
-        dot = fma(x, elem<ES>(center_row, c), dot);
-        na2 = fma(x, x, na2);
+  const int i = (int)(row % g.N);
+  const int words = g.d * ES / 4;
+  const int nk = (words + 63) / 64;  // words per lane in use
+  const uint32_t* base = reinterpret_cast<const uint32_t*>(X) + (bh * g.L + block_origin(g, i)) * (int64_t)words;
+  double acc[KW][2];
+#pragma unroll
+  for (int k = 0; k < KW; ++k) acc[k][0] = acc[k][1] = 0.0;
+#pragma unroll 1
+  for (int k = 0; k < nk; ++k) {  // (one pass for d <= 128 bf16 / d <= 64 fp32)
+    const int w = lane + 64 * k;
+    const bool live = w < words;
+    double a0 = 0.0, a1 = 0.0;
+    for (int r0 = 0; r0 < g.Bk; r0 += TB) {
+      uint32_t v[TB];
+#pragma unroll
+      for (int u = 0; u < TB; ++u)
+        v[u] = (live && r0 + u < g.Bk) ? base[(int64_t)koff[min(r0 + u, g.Bk - 1)] * words + w] : 0u;
+#pragma unroll
+      for (int u = 0; u < TB; ++u) {
+        if (r0 + u < g.Bk) {  // ascending intra-block id
+          if (ES == 4) {
+            a0 = __dadd_rn(a0, (double)__uint_as_float(v[u]));
+          } else {
+            double lo, hi;
+            unpack<ES>(v[u], lo, hi);
+            a0 = __dadd_rn(a0, lo);
+            a1 = __dadd_rn(a1, hi);
+          }
+        }
       }
+    }
+    if (live) {
+      const double bk = (double)g.Bk;
+      if (ES == 4) {
+        Xbar[row * g.d + w] = __ddiv_rn(a0, bk);
+      } else {
+        double2 o;
+        o.x = __ddiv_rn(a0, bk);
+        o.y = __ddiv_rn(a1, bk);
+        *reinterpret_cast<double2*>(Xbar + row * g.d + 2 * w) = o;
+      }
+    }
+  }
+  (void)acc;
+}
+
+// ------------------------------------------------------------------------------ pruning
+// Lane t owns token t of the block (Bk > 64: several passes).  The token rows pass through a
+// per-wavefront LDS tile in groups of up to 8 sixteen-byte chunks: loaded row-contiguous
+// (coalesced), read back one row per lane; the dot product with the center and the squared
+// norm accumulate over the channels in ascending order across the groups.
+constexpr int kGroup = 8;                          // chunks of a row staged at a time
+constexpr int kRowStride = kGroup * 16 + 16;       // LDS bytes per staged row (padded: lanes 16 apart share banks, the b128 minimum)
+constexpr int kTileBytes = 64 * kRowStride;
+
+__device__ inline void wave_lds_sync() {  // LDS written by other lanes of this wavefront becomes readable
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int ES>
+__global__ __launch_bounds__(64 * kWaves) void prune_kernel(Geom g, const uint8_t* Q, int n_keep,
+                                                           int32_t* keep_idx) {
+  __shared__ __align__(16) uint8_t tiles[kWaves][kTileBytes];
+  __shared__ __align__(16) uint8_t crow[kWaves][256 * 4];  // the center token's row
+  __shared__ double cosv[kWaves][256];
+  __shared__ int koff[256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int t = threadIdx.x; t < g.Bk; t += 64 * kWaves) koff[t] = intra_offset(g, t);
+  __syncthreads();  // the only workgroup barrier; wavefronts are independent from here on
+  const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
+  if (row >= g.rows) return;
+  const int64_t bh = row / g.N;
+  const int i = (int)(row % g.N);
+  const int row_bytes = g.d * ES, cpr = row_bytes / 16;
+  const uint8_t* base = Q + (bh * g.L + block_origin(g, i)) * (int64_t)row_bytes;
+  uint8_t* tile = tiles[wave];
+  uint8_t* cr = crow[wave];
+
+  for (int q = lane; q < cpr; q += 64)
+    *reinterpret_cast<uint4*>(cr + 16 * q) = *reinterpret_cast<const uint4*>(base + (int64_t)koff[g.center] * row_bytes + 16 * q);
+  wave_lds_sync();
+  constexpr int EPC = 16 / ES;  // channels per chunk
+  double nc2 = 0.0;             // |q_c|^2, same channel order in every lane
+  for (int q = 0; q < cpr; ++q) {
+    const uint4 cv = *reinterpret_cast<const uint4*>(cr + 16 * q);
+    const uint32_t cw[4] = {cv.x, cv.y, cv.z, cv.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (ES == 4) {
+        const double x = (double)__uint_as_float(cw[e]);
+        nc2 = fma(x, x, nc2);
+      } else {
+        double lo, hi;
+        unpack<ES>(cw[e], lo, hi);
+        nc2 = fma(lo, lo, nc2);
+        nc2 = fma(hi, hi, nc2);
+      }
+    }
+  }
+  (void)EPC;
+
+  for (int t0 = 0; t0 < g.Bk; t0 += 64) {
+    const int nt = min(64, g.Bk - t0);
+    double dot = 0.0, na2 = 0.0;
+    for (int q0 = 0; q0 < cpr; q0 += kGroup) {
+      const int nq = min(kGroup, cpr - q0);
+      wave_lds_sync();  // everyone is done reading the previous group
+      {  // all loads of the group first (at most 64 * kGroup / 64 = kGroup per lane), then the LDS writes
+        uint4 val[kGroup];
+#pragma unroll
+        for (int n = 0; n < kGroup; ++n) {
+          const int v = lane + 64 * n, r = min(v / nq, nt - 1), q = v - (v / nq) * nq;
+          val[n] = *reinterpret_cast<const uint4*>(base + (int64_t)koff[t0 + r] * row_bytes + 16 * (q0 + q));
+        }
+#pragma unroll
+        for (int n = 0; n < kGroup; ++n) {
+          const int v = lane + 64 * n, r = v / nq, q = v - r * nq;
+          if (v < nt * nq) *reinterpret_cast<uint4*>(tile + r * kRowStride + 16 * q) = val[n];
+        }
+      }
+      wave_lds_sync();
+      if (lane < nt) {
+        for (int q = 0; q < nq; ++q) {
+          const uint4 xv = *reinterpret_cast<const uint4*>(tile + lane * kRowStride + 16 * q);
+          const uint4 cv = *reinterpret_cast<const uint4*>(cr + 16 * (q0 + q));
+          const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w}, cw[4] = {cv.x, cv.y, cv.z, cv.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (ES == 4) {
+              const double x = (double)__uint_as_float(xw[e]);
+              dot = fma(x, (double)__uint_as_float(cw[e]), dot);
+              na2 = fma(x, x, na2);
+            } else {
+              double xl, xh, cl, ch;
+              unpack<ES>(xw[e], xl, xh);
+              unpack<ES>(cw[e], cl, ch);
+              dot = fma(xl, cl, dot);
+              na2 = fma(xl, xl, na2);
+              dot = fma(xh, ch, dot);
+              na2 = fma(xh, xh, na2);
+            }
+          }
+        }
+      }
+    }
+    if (lane < nt) {
       const double den = __dsqrt_rn(__dmul_rn(na2, nc2));
-      cosv[c0 + threadIdx.x] = den > 0.0 ? __ddiv_rn(dot, den) : 0.0;
+      cosv[wave][t0 + lane] = den > 0.0 ? __ddiv_rn(dot, den) : 0.0;
     }
   }
-  __syncthreads();
-  const int t = threadIdx.x;
-  int keep = 0;
-  if (t < g.Bk) {
-    if (t == g.center) {
-      keep = 1;
-    } else {
-      const double ct = cosv[t];
-      int rank = 0;  // tokens (center excluded) ordered before t: smaller cosine, then smaller id
-      for (int u = 0; u < g.Bk; ++u) {
-        if (u == g.center || u == t) continue;
-        const double cu = cosv[u];
-        rank += (cu < ct) || (cu == ct && u < t);
+  wave_lds_sync();
+
+  int base_pos = 0;  // retained tokens with a smaller id, over the passes so far
+  for (int t0 = 0; t0 < g.Bk; t0 += 64) {
+    const int t = t0 + lane;
+    bool keep = false;
+    if (t < g.Bk) {
+      if (t == g.center) {
+        keep = true;
+      } else {
+        const double ct = cosv[wave][t];
+        int rank = 0;  // tokens (center excluded) ordered before t: smaller cosine, then smaller id
+        for (int u = 0; u < g.Bk; ++u) {
+          const double cu = cosv[wave][u];
+          rank += (u != g.center && u != t) && ((cu < ct) || (cu == ct && u < t));
+        }
+        keep = rank < n_keep - 1;
       }
-      keep = rank < n_keep - 1;
     }
-  }
-  kept[t] = keep;
-  __syncthreads();
-  if (keep) {
-    int pos = 0;
-    for (int u = 0; u < t; ++u) pos += kept[u];
-    keep_idx[(int64_t)row * n_keep + pos] = t;
+    const unsigned long long m = __ballot(keep);
+    if (keep) keep_idx[row * n_keep + base_pos + __popcll(m & ((1ull << lane) - 1ull))] = t;
+    base_pos += __popcll(m);
   }
 }
 
 int launch_pool(const Geom& g, int dtype, const void* X, double* Xbar, hipStream_t st) {
   const uint8_t* x = static_cast<const uint8_t*>(X);
+  const dim3 grid((g.rows + kWaves - 1) / kWaves), block(64 * kWaves);
   if (dtype == BSA_F32)
-    hipLaunchKernelGGL(pool_kernel<4>, dim3(g.rows), dim3(kThreads), 0, st, g, x, Xbar);
+    hipLaunchKernelGGL(pool_kernel<4>, grid, block, 0, st, g, x, Xbar);
   else
-    hipLaunchKernelGGL(pool_kernel<2>, dim3(g.rows), dim3(kThreads), 0, st, g, x, Xbar);
+    hipLaunchKernelGGL(pool_kernel<2>, grid, block, 0, st, g, x, Xbar);
   return check_launch();
 }
 
 int launch_prune(const Geom& g, int dtype, const void* Q, int n_keep, int32_t* keep_idx, hipStream_t st) {
   const uint8_t* q = static_cast<const uint8_t*>(Q);
+  const dim3 grid((g.rows + kWaves - 1) / kWaves), block(64 * kWaves);
   if (dtype == BSA_F32)
-    hipLaunchKernelGGL(prune_kernel<4>, dim3(g.rows), dim3(kThreads), 0, st, g, q, n_keep, keep_idx);
+    hipLaunchKernelGGL(prune_kernel<4>, grid, block, 0, st, g, q, n_keep, keep_idx);
   else
-    hipLaunchKernelGGL(prune_kernel<2>, dim3(g.rows), dim3(kThreads), 0, st, g, q, n_keep, keep_idx);
+    hipLaunchKernelGGL(prune_kernel<2>, grid, block, 0, st, g, q, n_keep, keep_idx);
   return check_launch();
 }
 
