@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-heads", type=int, default=3, help="heads of the workload the CPU oracle is timed on")
+    ap.add_argument("--sweep", action="store_true",
+                    help="the sparsity sweep instead of the single benchmark: sigma x threshold x keep_ratio on the "
+                         "workload's shape, one JSON line per point (seed = point index)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain elementwise copy of this many MiB (read + write that much each), "
                          "the known-traffic dispatch that hardware-counter readings are scaled by")
@@ -105,6 +108,54 @@ def cpu_baseline(wl, heads: int):
     }
 
 
+def sweep(args, torch, B):
+    """Config 4: 3 noise levels x 4 mass thresholds x 3 keep ratios on the benchmark shape."""
+    from bsa_workloads import WORKLOADS
+
+    dev = torch.device("cuda:0")
+    base = WORKLOADS[args.workload]
+    point = 0
+    for sigma in (0.1, 0.3, 1.0):
+        for p in (0.5, 0.8, 0.9, 0.95):
+            for r in (0.25, 0.5, 1.0):
+                wl = base.replace(sigma=sigma, threshold=p, keep_ratio=r, seed=point)
+                shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16)
+                x = make_inputs(wl, torch)
+                Q, K, V, dO = x["Q"], x["K"], x["V"], x["dO"]
+                nk = B.n_keep(shp, r)
+                lists = B.alloc_kv_lists(shp, dev)
+                O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+                LSE = torch.empty((wl.B, wl.H, wl.L), dtype=torch.float32, device=dev)
+                ws = torch.empty(max(1, B.bwd_workspace_bytes(shp, nk)), dtype=torch.uint8, device=dev)
+                fws = torch.empty(max(1, B.fwd_workspace_bytes(shp, nk)), dtype=torch.uint8, device=dev)
+                state = {}
+
+                def indices():
+                    state["lists"] = B.select_kv(shp, B.pool_blocks(shp, Q), B.pool_blocks(shp, K), p, out=lists)
+                    state["keep"] = B.prune_q(shp, Q, r)
+
+                def fwd():
+                    B.attn_fwd(shp, Q, K, V, lists, state["keep"], O=O, LSE=LSE, workspace=fws)
+
+                def bwd():
+                    B.attn_bwd(shp, Q, K, V, O, LSE, dO, lists, state["keep"], dQ=dQ, dK=dK, dV=dV, workspace=ws)
+
+                indices(); fwd(); bwd()
+                t_idx, t_f, t_b = timed(torch, indices, args.steps), timed(torch, fwd, args.steps), timed(torch, bwd, args.steps)
+                nnz = int(lists.nnz.item())
+                f = nnz / (shp.rows * shp.N)
+                flops = 14.0 * wl.d * nk * shp.Bk * nnz
+                print(json.dumps({
+                    "point": point, "sigma": sigma, "threshold": p, "keep_ratio": r, "n_keep": nk,
+                    "selected_block_fraction": f, "sparsity": 1.0 - (nk / shp.Bk) * f,
+                    "ms_indices": t_idx, "ms_fwd": t_f, "ms_bwd": t_b, "ms_layer": t_idx + t_f + t_b,
+                    "actual_tflops": flops / ((t_f + t_b) * 1e-3) / 1e12,
+                    "effective_tflops": 14.0 * wl.B * wl.H * wl.L * wl.L * wl.d / ((t_idx + t_f + t_b) * 1e-3) / 1e12,
+                }), flush=True)
+                point += 1
+                del x, Q, K, V, dO, O, dQ, dK, dV, lists, ws, fws
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -115,6 +166,10 @@ def main():
     from bsa_workloads import WORKLOADS
     from paper_2509_01085_amd import binding as B
 
+    if args.sweep:
+        torch.cuda.set_device(0)
+        sweep(args, torch, B)
+        return
     wl = WORKLOADS[args.workload]
     over = {k: v for k, v in (("sigma", args.sigma), ("threshold", args.threshold), ("keep_ratio", args.keep_ratio)) if v is not None}
     if over:
