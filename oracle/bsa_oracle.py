@@ -11,6 +11,7 @@ Passages followed (paper section / equation):
   * block-level representations and inter-block scores .. Sec. 3.2.3
   * minimal cumulative-mass KV-block set ................ Sec. 3.2.3, Eq. 4
   * query pruning by cosine similarity to the center .... Sec. 3.2.2, Eq. 2
+  * window-based critical tokens ....................... Sec. 3.2.2 ("Critical Token")
   * token filling ...................................... Sec. 3.2.2 ("Token Filling")
   * sparse attention over selected queries / KV blocks .. Sec. 3.2.4, Eq. 5; mask of Sec. 3.1
   * backward ........................................... derived from Eq. 5 + token filling
@@ -21,7 +22,9 @@ the design notes): mean pooling of all tokens of a block; block logits scaled
 by 1/sqrt(d); a fixed probability-mass threshold p in Eq. 4 with p >= 1 meaning
 "all blocks"; ties broken toward the lower index; the center token is local
 coordinate (Ct//2, Ch//2, Cw//2), always kept and counted inside the quota
-ceil(r*|block|); cosine with a zero vector is 0; the softmax of Eq. 5 is
+ceil(r*|block|) (with windows: the same per window, center (Wt//2, Wh//2, Ww//2),
+quota ceil(r*|window|), fill from the window's own center); cosine with a zero
+vector is 0; the softmax of Eq. 5 is
 normalised over the selected keys only; selection and pruning are constants
 for the backward pass and the fill copy back-propagates into the center row.
 
@@ -56,12 +59,63 @@ class Partition:
     Ct: int
     Ch: int
     Cw: int
+    # Window of the critical-token mechanism (Sec. 3.2.2 "Critical Token"): every block is
+    # cut into windows (Wt, Wh, Ww) that divide it evenly, each with its own center token;
+    # 0 means the whole block is one window (a single critical token per block).
+    Wt: int = 0
+    Wh: int = 0
+    Ww: int = 0
 
     def __post_init__(self):
         if min(self.T, self.Hs, self.Ws, self.Ct, self.Ch, self.Cw) <= 0:
             raise ValueError("grid and block extents must be positive")
         if self.T % self.Ct or self.Hs % self.Ch or self.Ws % self.Cw:
             raise ValueError("block shape must divide the grid (Sec. 3.2.1)")
+        wt, wh, ww = self.window
+        if min(wt, wh, ww) <= 0 or self.Ct % wt or self.Ch % wh or self.Cw % ww:
+            raise ValueError("window shape must divide the block evenly (Sec. 3.2.2)")
+
+    @property
+    def window(self) -> Tuple[int, int, int]:
+        return (self.Wt or self.Ct, self.Wh or self.Ch, self.Ww or self.Cw)
+
+    @property
+    def Wk(self) -> int:
+        """Tokens per window."""
+        wt, wh, ww = self.window
+        return wt * wh * ww
+
+    @property
+    def nwin(self) -> int:
+        return self.Bk // self.Wk
+
+    def window_of(self) -> np.ndarray:
+        """win[c] = window (numbered raster-wise over the block's window grid) of intra-block token c."""
+        wt, wh, ww = self.window
+        nh, nw = self.Ch // wh, self.Cw // ww
+        win = np.empty(self.Bk, dtype=np.int64)
+        for ct in range(self.Ct):
+            for ch in range(self.Ch):
+                for cw in range(self.Cw):
+                    win[(ct * self.Ch + ch) * self.Cw + cw] = ((ct // wt) * nh + ch // wh) * nw + cw // ww
+        return win
+
+    def centers(self) -> np.ndarray:
+        """cen[w] = intra-block id of the critical token of window w: local coordinate
+        (Wt//2, Wh//2, Ww//2) inside the window."""
+        wt, wh, ww = self.window
+        nt, nh, nw = self.Ct // wt, self.Ch // wh, self.Cw // ww
+        cen = np.empty(self.nwin, dtype=np.int64)
+        for a in range(nt):
+            for b in range(nh):
+                for c in range(nw):
+                    ct, ch, cw = a * wt + wt // 2, b * wh + wh // 2, c * ww + ww // 2
+                    cen[(a * nh + b) * nw + c] = (ct * self.Ch + ch) * self.Cw + cw
+        return cen
+
+    def center_of(self) -> np.ndarray:
+        """For every intra-block token, the intra-block id of its window's critical token."""
+        return self.centers()[self.window_of()]
 
     @property
     def L(self) -> int:
@@ -82,13 +136,20 @@ class Partition:
 
     @property
     def center(self) -> int:
-        """Intra-block id of the critical (center) token."""
+        """Intra-block id of the critical (center) token of a block that is one window."""
+        if self.nwin != 1:
+            raise ValueError("a block with several windows has several critical tokens: use centers()")
         return (self.Ct // 2) * self.Ch * self.Cw + (self.Ch // 2) * self.Cw + (self.Cw // 2)
 
-    def n_keep(self, r: float) -> int:
+    def n_keep_window(self, r: float) -> int:
+        """Retained tokens per window: ceil(r * |window|) (Eq. 2 applied per window)."""
         if not (0.0 < r <= 1.0):
             raise ValueError("retained ratio r must lie in (0, 1] (Eq. 2)")
-        return int(ceil(r * self.Bk - 1e-12))
+        return int(ceil(r * self.Wk - 1e-12))
+
+    def n_keep(self, r: float) -> int:
+        """Retained tokens per block: the windows' quotas concatenated."""
+        return self.nwin * self.n_keep_window(r)
 
     def block_tokens(self) -> np.ndarray:
         """tok[i, c] = raster index of intra-block token c of block i.
@@ -212,13 +273,14 @@ def transpose_csr(ptr: np.ndarray, idx: np.ndarray, n_cols: int) -> Tuple[np.nda
 # Eq. 2: keep the ceil(r*Bk) tokens least similar to the block's center
 # --------------------------------------------------------------------------
 def cosine_to_center(Q: np.ndarray, part: Partition) -> np.ndarray:
-    """cos[i, c] between token c of block i and that block's center token."""
+    """cos[i, c] between token c of block i and the center token of c's window."""
     tok = part.block_tokens()
+    cof = part.center_of()
     Qb = np.asarray(Q, dtype=np.float64)[tok]  # [N, Bk, d]
-    qc = Qb[:, part.center:part.center + 1, :]
+    qc = Qb[:, cof, :]
     dot = _seq_dot(Qb, qc)
     nrm = _seq_dot(Qb, Qb)
-    nc = nrm[:, part.center:part.center + 1]
+    nc = nrm[:, cof]
     den = np.sqrt(nrm * nc)
     cos = np.zeros_like(dot)
     np.divide(dot, den, out=cos, where=den > 0.0)  # zero-norm vector: cos := 0
@@ -228,21 +290,28 @@ def cosine_to_center(Q: np.ndarray, part: Partition) -> np.ndarray:
 def prune_q(Q: np.ndarray, part: Partition, r: float) -> Tuple[np.ndarray, float]:
     """keep_idx[i, :] = ascending intra-block ids of the retained queries of block i.
 
-    The center is always retained and counts toward the quota; the other
-    n_keep-1 are the tokens with the smallest cosine (ties: lower id first).
-    Also returns the smallest gap between the last kept and first pruned cosine."""
-    n_keep = part.n_keep(r)
+    Per window: its center is always retained and counts toward the window's quota
+    kw = ceil(r*|window|); the other kw-1 are the window's tokens with the smallest
+    cosine to that center (ties: lower id first).  The windows' selections are
+    concatenated.  Also returns the smallest gap between the last kept and the
+    first pruned cosine of any window."""
+    kw = part.n_keep_window(r)
     cos = cosine_to_center(Q, part)
-    keep = np.empty((part.N, n_keep), dtype=np.int32)
+    win, cen = part.window_of(), part.centers()
+    keep = np.empty((part.N, part.nwin * kw), dtype=np.int32)
     gap = float("inf")
-    others = np.array([c for c in range(part.Bk) if c != part.center])
     for i in range(part.N):
-        co = cos[i, others]
-        order = others[np.lexsort((others, co))]  # cosine ascending, then id ascending
-        kept = order[: n_keep - 1]
-        keep[i] = np.sort(np.concatenate([[part.center], kept]))
-        if 1 <= n_keep - 1 < len(order):
-            gap = min(gap, float(cos[i, order[n_keep - 1]] - cos[i, order[n_keep - 2]]))
+        sel = []
+        for w in range(part.nwin):
+            others = np.array([c for c in range(part.Bk) if win[c] == w and c != cen[w]], dtype=np.int64)
+            sel.append(cen[w])
+            if len(others) == 0:
+                continue
+            order = others[np.lexsort((others, cos[i, others]))]  # cosine ascending, then id ascending
+            sel.extend(order[: kw - 1])
+            if 1 <= kw - 1 < len(order):
+                gap = min(gap, float(cos[i, order[kw - 1]] - cos[i, order[kw - 2]]))
+        keep[i] = np.sort(np.array(sel))
     return keep, gap
 
 
@@ -268,6 +337,7 @@ def attn_fwd(Q, K, V, part: Partition, q2k_ptr, q2k_idx, keep_idx, sm_scale: flo
     output and log-sum-exp (token filling).  Returns O[L, d], LSE[L]; if
     `q_blocks` is given only those blocks' rows are computed (others stay 0)."""
     tok = part.block_tokens()
+    cof = part.center_of()
     Q = np.asarray(Q, dtype=dtype)
     K = np.asarray(K, dtype=dtype)
     V = np.asarray(V, dtype=dtype)
@@ -277,8 +347,8 @@ def attn_fwd(Q, K, V, part: Partition, q2k_ptr, q2k_idx, keep_idx, sm_scale: flo
         rows = tok[i, keep_idx[i]]
         keys = tok[q2k_idx[q2k_ptr[i]:q2k_ptr[i + 1]]].reshape(-1)
         o, lse, _ = attend_block(Q[rows], K[keys], V[keys], sm_scale)
-        cpos = int(np.nonzero(keep_idx[i] == part.center)[0][0])
-        O[tok[i]] = o[cpos]  # fill every token of the block with the center's output ...
+        cpos = np.searchsorted(keep_idx[i], cof)  # position of each token's window center among the retained rows
+        O[tok[i]] = o[cpos]  # fill every token with its window center's output ...
         LSE[tok[i]] = lse[cpos]
         O[rows] = o  # ... then overwrite the retained ones with their own
         LSE[rows] = lse
@@ -311,11 +381,12 @@ def attn_fwd_dense_masked(Q, K, V, part: Partition, q2k_ptr, q2k_idx, keep_idx, 
 
 
 def fill_source(part: Partition, keep_idx) -> np.ndarray:
-    """src[n] = n for a retained token, the raster index of its block's center otherwise."""
+    """src[n] = n for a retained token, the raster index of its window's center otherwise."""
     tok = part.block_tokens()
+    cof = part.center_of()
     src = np.empty(part.L, dtype=np.int64)
     for i in range(part.N):
-        src[tok[i]] = tok[i, part.center]
+        src[tok[i]] = tok[i, cof]
         src[tok[i, keep_idx[i]]] = tok[i, keep_idx[i]]
     return src
 
@@ -324,13 +395,14 @@ def fill_source(part: Partition, keep_idx) -> np.ndarray:
 # backward of (Eq. 5 + token filling), indices held constant
 # --------------------------------------------------------------------------
 def folded_grad(dO: np.ndarray, part: Partition, keep_idx, i: int, tok=None) -> np.ndarray:
-    """g for the retained rows of block i: dO of the row itself, and for the
-    center additionally the dO of every pruned token it was copied to."""
+    """g for the retained rows of block i: dO of the row itself, and for a window's
+    center additionally the dO of every pruned token of that window (it was copied to them)."""
     tok = part.block_tokens() if tok is None else tok
+    cof = part.center_of()
     g = np.array(dO[tok[i, keep_idx[i]]])
     pruned = np.setdiff1d(np.arange(part.Bk), keep_idx[i])
-    cpos = int(np.nonzero(keep_idx[i] == part.center)[0][0])
     for c in pruned:  # ascending intra-block id
+        cpos = int(np.searchsorted(keep_idx[i], cof[c]))
         g[cpos] = g[cpos] + dO[tok[i, c]]
     return g
 

@@ -379,3 +379,102 @@ def test_backward_with_stored_output_equals_exact_backward_when_storage_is_exact
     # a perturbed stored O changes dQ and dK through delta only, never dV
     bumped = o.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], *args, O_in=O + 1e-3)
     assert np.array_equal(bumped[2], exact[2]) and np.abs(bumped[0] - exact[0]).max() > 1e-6
+
+
+# ------------------------------------------- window-based critical tokens (Sec. 3.2.2)
+def win_part():
+    """The tiny grid with its 2x4x4 blocks cut into (1,2,2) windows: 8 windows of 4 tokens."""
+    return o.Partition(*TINY.grid, *TINY.block, 1, 2, 2)
+
+
+def _window_center_by_coordinates(part, n):
+    """Raster index of the critical token of raster token n's window, from coordinates alone."""
+    wt, wh, ww = part.window
+    t, h, w = n // (part.Hs * part.Ws), (n // part.Ws) % part.Hs, n % part.Ws
+    lt, lh, lw = t % part.Ct, h % part.Ch, w % part.Cw  # local coordinates inside the block
+    ct = t - lt + (lt // wt) * wt + wt // 2
+    ch = h - lh + (lh // wh) * wh + wh // 2
+    cw = w - lw + (lw // ww) * ww + ww // 2
+    return (ct * part.Hs + ch) * part.Ws + cw
+
+
+def test_window_tables_of_the_papers_default():
+    lines = open(__file__.replace("test_oracle_pins.py", "golden/paper_constants.txt")).read().split("\n")
+    vals = dict(l.split("=")[0:2] for l in lines if "=" in l and not l.startswith("#"))
+    block = tuple(int(v) for v in vals["block"].split(","))
+    window = tuple(int(v) for v in vals["window"].split(","))
+    part = o.Partition(*block, *block, *window)  # one block
+    assert (part.nwin, part.Wk) == (8, 8)
+    # Sec. 4.1: r = 0.5 still gives a query block of 32 with (2,2,2) windows (4 of 8 per window)
+    assert part.n_keep(float(vals["keep_ratio"])) == int(vals["query_block_size"].split()[0])
+    win, cen = part.window_of(), part.centers()
+    assert win[0] == 0 and win[63] == 7 and win[2] == 1 and win[8] == 2 and win[32] == 4
+    assert cen.tolist() == [21, 23, 29, 31, 53, 55, 61, 63]  # local (1,1,1) of each 2x2x2 window
+    assert sorted(np.bincount(win).tolist()) == [8] * 8
+    tok = part.block_tokens()
+    for c in range(64):
+        assert tok[0, part.center_of()[c]] == _window_center_by_coordinates(part, tok[0, c])
+    with pytest.raises(ValueError):
+        o.Partition(4, 4, 4, 4, 4, 4, 3, 2, 2)  # must divide the block evenly
+
+
+def test_window_equal_to_the_block_is_the_single_center_method():
+    x = tiny_inputs()
+    a, _ = o.prune_q(x["Q"], tiny_part(), 0.5)
+    b, _ = o.prune_q(x["Q"], o.Partition(*TINY.grid, *TINY.block, *TINY.block), 0.5)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("r", [0.25, 0.5, 0.75, 1.0])
+def test_window_prune_invariants(r):
+    part = win_part()
+    x = tiny_inputs()
+    keep, _ = o.prune_q(x["Q"], part, r)
+    kw = ceil(r * part.Wk - 1e-12)
+    assert keep.shape == (part.N, part.nwin * kw)
+    tok = part.block_tokens()
+    win, cen = part.window_of(), part.centers()
+    for i in range(part.N):
+        ks = keep[i].tolist()
+        assert ks == sorted(set(ks))
+        for w in range(part.nwin):
+            members = [c for c in range(part.Bk) if win[c] == w]
+            kept = [c for c in members if c in ks]
+            assert len(kept) == kw and cen[w] in kept  # every window fills its own quota, center included
+            qc = x["Q"][tok[i, cen[w]]]
+            cos = {c: float(x["Q"][tok[i, c]] @ qc / (np.linalg.norm(x["Q"][tok[i, c]]) * np.linalg.norm(qc))) for c in members}
+            pruned = [c for c in members if c not in ks]
+            kept_others = [c for c in kept if c != cen[w]]
+            if pruned and kept_others:
+                assert max(cos[c] for c in kept_others) <= min(cos[c] for c in pruned) + 1e-12
+
+
+@pytest.mark.parametrize("p,r", [(0.9, 0.5), (0.5, 0.25)])
+def test_window_fwd_bwd_against_autograd_of_masked_dense_form(p, r):
+    """As the single-center test, with the fill map built from window coordinates here."""
+    part = win_part()
+    x = tiny_inputs(1)
+    x["Q"], x["K"] = x["Q"] * 3.0, x["K"] * 3.0
+    scale = 1 / sqrt(TINY.d)
+    ix, O, LSE, dQ, dK, dV = o.bsa_head(x["Q"], x["K"], x["V"], x["dO"], part, p, r)
+    tok = part.block_tokens()
+    src = np.empty(part.L, dtype=np.int64)
+    for i in range(part.N):
+        kept = set(tok[i, ix.keep_idx[i]].tolist())
+        for n in tok[i]:
+            src[n] = n if n in kept else _window_center_by_coordinates(part, n)
+    assert np.array_equal(src, o.fill_source(part, ix.keep_idx))
+    M = o.dense_mask(part, ix.q2k_ptr, ix.q2k_idx)
+    tO, tL, tdQ, tdK, tdV = _torch_dense(x["Q"], x["K"], x["V"], x["dO"], scale, M, src)
+    for a, b in ((O, tO), (LSE, tL), (dQ, tdQ), (dK, tdK), (dV, tdV)):
+        assert np.abs(a - b).max() < 1e-11 * max(1.0, np.abs(b).max())
+    # every center keeps its own gradient plus its window's fill copies: column sums are conserved
+    assert np.abs(dV.sum(axis=0) - x["dO"].sum(axis=0)).max() < 1e-10
+    pruned_any = False
+    for i in range(part.N):
+        for c in range(part.Bk):
+            if c not in ix.keep_idx[i]:
+                pruned_any = True
+                assert np.array_equal(O[tok[i, c]], O[_window_center_by_coordinates(part, tok[i, c])])
+                assert not dQ[tok[i, c]].any()
+    assert pruned_any
