@@ -92,7 +92,7 @@ def cpu_baseline(wl, heads: int):
     from bsa_workloads import head_inputs
     from oracle import bsa_oracle as o
 
-    part = o.Partition(*wl.grid, *wl.block)
+    part = o.Partition(*wl.grid, *wl.block, *wl.window)
     dtype = np.float64 if wl.L <= 4096 else np.float32  # attention GEMMs; decisions are always fp64
     t = 0.0
     for h in range(heads):
@@ -119,7 +119,7 @@ def sweep(args, torch, B):
         for p in (0.5, 0.8, 0.9, 0.95):
             for r in (0.25, 0.5, 1.0):
                 wl = base.replace(sigma=sigma, threshold=p, keep_ratio=r, seed=point)
-                shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16)
+                shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16, *wl.window)
                 x = make_inputs(wl, torch)
                 Q, K, V, dO = x["Q"], x["K"], x["V"], x["dO"]
                 nk = B.n_keep(shp, r)
@@ -174,7 +174,7 @@ def main():
     over = {k: v for k, v in (("sigma", args.sigma), ("threshold", args.threshold), ("keep_ratio", args.keep_ratio)) if v is not None}
     if over:
         wl = wl.replace(**over)
-    shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16)
+    shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16, *wl.window)
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     x = make_inputs(wl, torch)

@@ -36,6 +36,7 @@ class Workload:
     threshold: float = 0.9
     keep_ratio: float = 0.5
     seed: int = 0
+    window: Tuple[int, int, int] = (0, 0, 0)  # critical-token window; zeros = the whole block
 
     @property
     def L(self) -> int:
@@ -51,7 +52,8 @@ class Workload:
 
     @property
     def n_keep(self) -> int:
-        return int(ceil(self.keep_ratio * self.Bk - 1e-12))
+        wk = (self.window[0] or self.block[0]) * (self.window[1] or self.block[1]) * (self.window[2] or self.block[2])
+        return (self.Bk // wk) * int(ceil(self.keep_ratio * wk - 1e-12))
 
     def replace(self, **kw) -> "Workload":
         from dataclasses import replace as _r
@@ -64,6 +66,8 @@ WORKLOADS: Dict[str, Workload] = {
     "tiny": Workload("tiny", 1, 2, 64, "fp32", (4, 8, 8), (2, 4, 4)),
     # Wan-1.3B-shaped layer, 33,280 tokens, 520 blocks of 64.
     "wan1p3b": Workload("wan1p3b", 1, 12, 128, "bf16", (20, 32, 52), (4, 4, 4)),
+    # the same layer with the paper's default critical-token windows, (2,2,2) inside each block
+    "wan1p3b_win": Workload("wan1p3b_win", 1, 12, 128, "bf16", (20, 32, 52), (4, 4, 4), window=(2, 2, 2)),
     # 720p-shaped layer, 70,400 tokens, 1,100 blocks.
     "hd720p": Workload("hd720p", 1, 40, 128, "bf16", (20, 44, 80), (4, 4, 4)),
     # long-sequence layer, 161,280 tokens, 2,520 blocks.

@@ -6,7 +6,7 @@
  * (Sec. 3.2.2, Eq. 2) and every query block attends only to the minimal set of KV blocks
  * whose pooled softmax mass reaches a threshold (Sec. 3.2.3, Eq. 4); exact softmax
  * attention then runs over the survivors (Sec. 3.2.4, Eq. 5) and pruned positions are
- * filled with their block center's output (Sec. 3.2.2, "Token Filling").
+ * filled with the output of their window's critical token (Sec. 3.2.2, "Token Filling").
  *
  * Conventions shared by every entry point
  *   - All data pointers are DEVICE pointers on the current HIP device unless stated,
@@ -53,13 +53,19 @@ typedef struct bsa_shape {
   int32_t Ct, Ch, Cw;    /* 3D block shape (Sec. 3.2.1) */
   int32_t d;             /* head dimension, multiple of 8, <= 256 */
   int32_t dtype;         /* enum bsa_dtype of Q/K/V/O and the gradients */
+  int32_t Wt, Wh, Ww;    /* window of the critical-token mechanism (Sec. 3.2.2, "Critical Token"):
+                            must divide (Ct, Ch, Cw) evenly; 0,0,0 = the whole block, one critical
+                            token per block.  Windows are numbered raster-wise over the block's
+                            window grid; a window's critical token is its local (Wt/2, Wh/2, Ww/2). */
 } bsa_shape_t;
 
 /* Limits: Bk <= 256, N <= 8192, d % 8 == 0 and d <= 256. */
 
 const char* bsa_strerror(int status);
 
-/* Number of retained queries per block, ceil(keep_ratio * Bk) (Eq. 2); <0 on bad arguments. */
+/* Number of retained queries per block (Eq. 2): every window keeps ceil(keep_ratio * Wk) of
+ * its Wk tokens, so nwin * ceil(keep_ratio * Wk); ceil(keep_ratio * Bk) with one window.
+ * <0 on bad arguments. */
 int bsa_n_keep(const bsa_shape_t* shape, double keep_ratio);
 
 /*
@@ -94,10 +100,12 @@ int bsa_select_kv(const bsa_shape_t* shape, const double* Qbar, const double* Kb
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Sparse Query (Sec. 3.2.2, Eq. 2).  Per block: cosine similarity (fp64) of every token to
- * the center token, local coordinate (Ct/2, Ch/2, Cw/2); the center plus the n_keep-1
- * other tokens with the smallest cosine are retained (ties: lower intra-block id first;
- * a zero vector has cosine 0).  n_keep = ceil(keep_ratio * Bk).
+ * Sparse Query (Sec. 3.2.2, Eq. 2, and "Critical Token").  Per window of every block (the
+ * whole block when shape.Wt/Wh/Ww are 0): cosine similarity (fp64) of every token of the
+ * window to the window's critical token, local coordinate (Wt/2, Wh/2, Ww/2); the critical
+ * token plus the other ceil(keep_ratio * Wk) - 1 tokens of the window with the smallest
+ * cosine are retained (ties: lower intra-block id first; a zero vector has cosine 0).
+ * n_keep = nwin * ceil(keep_ratio * Wk): the windows' selections concatenated.
  *   keep_idx out [B,H,N,n_keep] int32  intra-block ids, ascending
  */
 int bsa_prune_q(const bsa_shape_t* shape, const void* Q, double keep_ratio,
@@ -106,10 +114,12 @@ int bsa_prune_q(const bsa_shape_t* shape, const void* Q, double keep_ratio,
 /*
  * Sparse attention forward with token filling (Eq. 5; Sec. 3.2.2 "Token Filling").
  * Retained queries of block i attend, with exact softmax at scale sm_scale, to all Bk
- * tokens of every KV block listed for row i; pruned positions receive the center's row.
+ * tokens of every KV block listed for row i; a pruned position receives the row of its
+ * window's critical token.
  *   O   out [B,H,L,d] shape.dtype,  LSE out [B,H,L] float (natural-log sum-exp, filled too)
  * Every row must list at least one KV block (Eq. 4 always selects one).
- * keep_idx rows must be ascending, distinct, in [0,Bk) and contain the center.
+ * keep_idx rows must be ascending, distinct, in [0,Bk) and contain every window's critical
+ * token (a window whose critical token is missing is left unfilled).
  *   workspace   bsa_fwd_workspace_bytes(shape, n_keep) bytes of device scratch (may be NULL
  *               when that is 0), else BSA_ERR_WORKSPACE.  It holds the partial results of
  *               the query blocks whose KV walk is split over several workgroups to balance a

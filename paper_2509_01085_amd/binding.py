@@ -33,7 +33,7 @@ class BsaError(RuntimeError):
 
 
 class ShapeStruct(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("B", "H", "T", "Hs", "Ws", "Ct", "Ch", "Cw", "d", "dtype")]
+    _fields_ = [(n, C.c_int32) for n in ("B", "H", "T", "Hs", "Ws", "Ct", "Ch", "Cw", "d", "dtype", "Wt", "Wh", "Ww")]
 
 
 _lib = None
@@ -84,6 +84,9 @@ class Shape:
     Cw: int
     d: int
     dtype: int  # F32 or BF16
+    Wt: int = 0  # window of the critical-token mechanism; 0, 0, 0 = the whole block
+    Wh: int = 0
+    Ww: int = 0
 
     @property
     def L(self) -> int:
@@ -106,7 +109,8 @@ class Shape:
         return torch.float32 if self.dtype == F32 else torch.bfloat16
 
     def c(self) -> ShapeStruct:
-        return ShapeStruct(self.B, self.H, self.T, self.Hs, self.Ws, self.Ct, self.Ch, self.Cw, self.d, self.dtype)
+        return ShapeStruct(self.B, self.H, self.T, self.Hs, self.Ws, self.Ct, self.Ch, self.Cw, self.d, self.dtype,
+                           self.Wt, self.Wh, self.Ww)
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:

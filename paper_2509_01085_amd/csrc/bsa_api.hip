@@ -27,19 +27,30 @@ int make_geom(const bsa_shape_t* s, Geom* g) {
   g->Ct = s->Ct; g->Ch = s->Ch; g->Cw = s->Cw; g->d = s->d;
   g->Nt = s->T / s->Ct; g->Nh = s->Hs / s->Ch; g->Nw = s->Ws / s->Cw;
   g->Bk = (int)Bk; g->N = (int)N; g->L = (int)L; g->rows = (int)rows;
-  g->center = (s->Ct / 2) * s->Ch * s->Cw + (s->Ch / 2) * s->Cw + (s->Cw / 2);
+  // windows of the critical-token mechanism must divide the block evenly (Sec. 3.2.2); 0 = the block
+  if (s->Wt < 0 || s->Wh < 0 || s->Ww < 0) return BSA_ERR_SHAPE;
+  g->Wt = s->Wt ? s->Wt : s->Ct; g->Wh = s->Wh ? s->Wh : s->Ch; g->Ww = s->Ww ? s->Ww : s->Cw;
+  if (s->Ct % g->Wt || s->Ch % g->Wh || s->Cw % g->Ww) return BSA_ERR_SHAPE;
+  g->Wk = g->Wt * g->Wh * g->Ww;
+  g->nwin = g->Bk / g->Wk;
   g->dense = 0;
   g->inv_Nw = g->Nw == 1 ? 0u : (uint32_t)(0x100000000ull / (uint32_t)g->Nw) + 1u;
   g->inv_NwNh = g->Nw * g->Nh == 1 ? 0u : (uint32_t)(0x100000000ull / (uint32_t)(g->Nw * g->Nh)) + 1u;
   return BSA_OK;
 }
 
-static int n_keep_of(const Geom& g, double r) {
+// retained tokens per window, ceil(r * Wk); per block it is nwin times that
+static int window_quota(const Geom& g, double r) {
   if (!(r > 0.0) || !(r <= 1.0)) return BSA_ERR_RANGE;
-  int n = (int)std::ceil(r * g.Bk - 1e-12);
+  int n = (int)std::ceil(r * g.Wk - 1e-12);
   if (n < 1) n = 1;
-  if (n > g.Bk) n = g.Bk;
+  if (n > g.Wk) n = g.Wk;
   return n;
+}
+
+static int n_keep_of(const Geom& g, double r) {
+  const int kw = window_quota(g, r);
+  return kw < 0 ? kw : kw * g.nwin;
 }
 
 }  // namespace bsa
@@ -106,9 +117,9 @@ int bsa_prune_q(const bsa_shape_t* shape, const void* Q, double keep_ratio, int3
   int rc = make_geom(shape, &g);
   if (rc) return rc;
   if (!Q || !keep_idx) return BSA_ERR_NULL;
-  int nk = n_keep_of(g, keep_ratio);
-  if (nk < 0) return nk;
-  return launch_prune(g, shape->dtype, Q, nk, keep_idx, (hipStream_t)stream);
+  const int kw = window_quota(g, keep_ratio);
+  if (kw < 0) return kw;
+  return launch_prune(g, shape->dtype, Q, kw, keep_idx, (hipStream_t)stream);
 }
 
 size_t bsa_fwd_workspace_bytes(const bsa_shape_t* shape, int n_keep) {

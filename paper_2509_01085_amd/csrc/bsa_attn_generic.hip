@@ -69,9 +69,8 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Geom g, AttnArgs a) {
   float* vs = ks + KT * ld;       // [KT][ld]
   float* ps = vs + KT * ld;       // [QT][KT+1]
   __shared__ int qtok[QT], ktok[KT];
-  __shared__ int keepflag[256];
-  __shared__ int cpos_s;
-  __shared__ float cen_lse;
+  __shared__ int keeppos[256];  // position of an intra-block token among the retained rows, -1 if pruned
+  __shared__ float lse_s[QT];
   const int tid = threadIdx.x;
   const int64_t row = blockIdx.x;
   const int64_t bh = row / g.N;
@@ -84,14 +83,9 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Geom g, AttnArgs a) {
   T* Oh = static_cast<T*>(a.O_out) + bh * g.L * g.d;
   float* Lh = a.LSE_out + bh * g.L;
 
-  keepflag[tid] = 0;
-  if (tid == 0) cpos_s = -1;
+  keeppos[tid] = -1;
   __syncthreads();
-  if (tid < a.n_keep) {
-    const int c = kept_id(g, a.keep_idx, row, a.n_keep, tid);
-    keepflag[c] = 1;
-    if (!g.dense && c == g.center && tid >= q0 && tid < q0 + nq) cpos_s = tid - q0;
-  }
+  if (tid < a.n_keep) keeppos[kept_id(g, a.keep_idx, row, a.n_keep, tid)] = tid;
   if (tid < QT) qtok[tid] = tid < nq ? token_of(g, i, kept_id(g, a.keep_idx, row, a.n_keep, q0 + tid)) : 0;
   __syncthreads();
   load_rows<T>(qs, ld, Qh, qtok, QT, nq, g.d);
@@ -144,26 +138,35 @@ __global__ __launch_bounds__(256) void fwd_generic_kernel(Geom g, AttnArgs a) {
       if (c < g.d) {
         const float val = o[cc] * inv;
         store_f32<T>(Oh + (int64_t)qtok[qi] * g.d + c, val);
-        if (qi == cpos_s) qs[c] = val;  // center row parked in LDS for the fill
+        qs[qi * ld + c] = val;  // output rows parked in LDS (over the query rows) for the fill
       }
     }
     if (kt == 0) {
       Lh[qtok[qi]] = lse;
-      if (qi == cpos_s) cen_lse = lse;
+      lse_s[qi] = lse;
     }
   }
   __syncthreads();
-  if (cpos_s >= 0) {  // token filling: every pruned token of the block takes the center's row
+  // token filling: a pruned token takes the row of its window's critical token; the workgroup
+  // whose query tile holds that row writes it
+  if (!g.dense) {
     for (int e = tid; e < g.Bk * g.d; e += 256) {
       const int c = e / g.d, ch = e % g.d;
-      if (!keepflag[c]) store_f32<T>(Oh + (int64_t)token_of(g, i, c) * g.d + ch, qs[ch]);
+      if (keeppos[c] >= 0) continue;
+      const int p = keeppos[center_of(g, c)] - q0;
+      if (p >= 0 && p < nq && keeppos[center_of(g, c)] >= 0)
+        store_f32<T>(Oh + (int64_t)token_of(g, i, c) * g.d + ch, qs[p * ld + ch]);
     }
-    if (tid < g.Bk && !keepflag[tid]) Lh[token_of(g, i, tid)] = cen_lse;
+    if (tid < g.Bk && keeppos[tid] < 0) {
+      const int p = keeppos[center_of(g, tid)] - q0;
+      if (p >= 0 && p < nq && keeppos[center_of(g, tid)] >= 0) Lh[token_of(g, i, tid)] = lse_s[p];
+    }
   }
 }
 
 // ------------------------------------------------------------- backward: preprocess
-// g = dO of the retained row (+ dO of every pruned token for the center row, ascending id);
+// g = dO of the retained row (+ for a window's critical token the dO of every pruned token of
+// that window, ascending id);
 // delta = <g, o>.  One wavefront per retained row, lanes over channels.
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_pre_generic_kernel(Geom g, AttnArgs a, GenericWs w) {
@@ -184,9 +187,9 @@ __global__ __launch_bounds__(256) void bwd_pre_generic_kernel(Geom g, AttnArgs a
     float part = 0.f;
     for (int ch = lane; ch < g.d; ch += 64) {
       float gv = load_f32<T>(dOh + tok * g.d + ch);
-      if (!g.dense && c == g.center)
+      if (!g.dense && c == center_of(g, c))  // a critical token: plus the dO of its window's pruned tokens
         for (int u = 0; u < g.Bk; ++u)
-          if (!keepflag[u]) gv += load_f32<T>(dOh + (int64_t)token_of(g, i, u) * g.d + ch);
+          if (!keepflag[u] && window_of(g, u) == window_of(g, c)) gv += load_f32<T>(dOh + (int64_t)token_of(g, i, u) * g.d + ch);
       w.g[(row * a.n_keep + kp) * g.d + ch] = gv;
       part += gv * load_f32<T>(Oh + tok * g.d + ch);
     }

@@ -12,8 +12,8 @@
 //                  workgroups per CU: while one waits at its barrier the other multiplies;
 //   n_keep  > 32 : eight wavefronts, two per query block splitting its queries, four tiles
 //                  in the ring, one workgroup per CU (also the dense baseline's shape).
-// Token filling (Sec. 3.2.2) happens in the epilogue: the center's row is parked in LDS and
-// copied to the block's pruned positions.
+// Token filling (Sec. 3.2.2) happens in the epilogue: the rows of the critical tokens (one per
+// window of the block) are parked in LDS and copied to their windows' pruned positions.
 #include <math.h>
 
 #include "bsa_mfma.h"
@@ -168,8 +168,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
   uint8_t* ring = smem;                                                  // [NB][K tile | V tile]
   uint32_t* masks = reinterpret_cast<uint32_t*>(smem + NB * 2 * TILE);   // [PG][W]
   __shared__ int koff[PBK];
-  __shared__ __align__(16) uint16_t cen_row[PG][D];
-  __shared__ float cen_lse[PG];
+  __shared__ float cen_lse[PG][PBK];  // per window
   __shared__ uint32_t keepbits[PG][2];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -403,12 +402,17 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
     BSA_TRACE_END();
     return;
   }
-  // epilogue: normalise, store the retained rows, park the center's row for the fill
+  // epilogue: normalise, store the retained rows, park the rows of the windows' critical tokens
+  // (in the tile ring, idle now) for the fill
+  uint16_t* cen_rows = reinterpret_cast<uint16_t*>(smem);  // [PG][nwin][D]
   const float ltot = l + xor32(l);
   const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
   const float lse = ltot > 0.f ? (m + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
+  __syncthreads();  // every wavefront is done with the ring
   if (qid >= 0) {
-    const bool is_center = !g.dense && qid == g.center;
+    const int win = window_of(g, qid);
+    const bool is_center = !g.dense && qid == window_center(g, win);
+    uint16_t* park = cen_rows + ((size_t)qb * g.nwin + win) * D;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -418,23 +422,27 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
         v.y = pack_bf16(o[dt][4 * r4 + 2] * inv, o[dt][4 * r4 + 3] * inv);
         const int ch = 32 * dt + 8 * r4 + 4 * grp;
         *reinterpret_cast<u32x2*>(Oh + (int64_t)qtok * D + ch) = v;
-        if (is_center) *reinterpret_cast<u32x2*>(&cen_row[qb][ch]) = v;
+        if (is_center) *reinterpret_cast<u32x2*>(park + ch) = v;
       }
     if (grp == 0) {
       Lh[qtok] = lse;
-      if (is_center) cen_lse[qb] = lse;
+      if (is_center) cen_lse[qb][win] = lse;
     }
   }
   __syncthreads();
-  // token filling: lane c of the block's first wavefront owns intra-block token c
+  // token filling: lane c of the block's first wavefront owns intra-block token c and, if it
+  // was pruned, copies the row of its window's critical token
   if (valid && !g.dense && sub == 0) {
     const bool kept = (keepbits[qb][lane >> 5] >> (lane & 31)) & 1u;
-    if (!kept) {
+    const int win = window_of(g, lane);
+    const bool have = (keepbits[qb][window_center(g, win) >> 5] >> (window_center(g, win) & 31)) & 1u;
+    if (!kept && have) {
       const int64_t tok = block_origin(g, i) + koff[lane];
+      const uint16_t* src = cen_rows + ((size_t)qb * g.nwin + win) * D;
 #pragma unroll
       for (int q = 0; q < D / 8; ++q)
-        *reinterpret_cast<u32x4*>(Oh + tok * D + 8 * q) = *reinterpret_cast<const u32x4*>(&cen_row[qb][8 * q]);
-      Lh[tok] = cen_lse[qb];
+        *reinterpret_cast<u32x4*>(Oh + tok * D + 8 * q) = *reinterpret_cast<const u32x4*>(src + 8 * q);
+      Lh[tok] = cen_lse[qb][win];
     }
   }
   if (!COMBINE) { BSA_TRACE_END(); }
@@ -472,10 +480,14 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
   using R = BwdRec<D, NQT>;
   constexpr int CPR = D / 8;       // 16-byte chunks per row
   constexpr int RPP = 256 / CPR;   // rows covered by one pass of the workgroup (a row = CPR adjacent lanes)
-  __shared__ __align__(16) float fold[RPP][D];  // column sums of the pruned tokens' dO, per row group
+  extern __shared__ __align__(16) float fold_mem[];
+  float* partial = fold_mem;                // [RPP][D] column sums of pruned dO rows, per row group
+  float* foldw = fold_mem + RPP * D;        // [nwin][D] the same, complete, per window
   __shared__ int keepflag[PBK];
   __shared__ int qtok[R::NQ];
+  __shared__ short qwin[R::NQ];   // window whose critical token the retained row is, or -1
   __shared__ int koff[PBK];
+  __shared__ short wtok[PBK];     // tokens grouped by window, ascending id inside a window
   const int tid = threadIdx.x;
   const int c = tid % CPR, rg = tid / CPR;
   const int64_t row = blockIdx.x;
@@ -491,39 +503,59 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
   if (tid < PBK) {
     koff[tid] = intra_offset(g, tid);
     keepflag[tid] = 0;
+    if (!g.dense) {  // position of token tid inside its window: raster order of its local coordinates
+      const int cw = tid % g.Cw, ch = (tid / g.Cw) % g.Ch, ct = tid / (g.Cw * g.Ch);
+      const int k = ((ct % g.Wt) * g.Wh + ch % g.Wh) * g.Ww + cw % g.Ww;
+      wtok[window_of(g, tid) * g.Wk + k] = (short)tid;
+    }
   }
   __syncthreads();
   if (tid < R::NQ) {
     int k = -1;
     if (tid < a.n_keep) k = g.dense ? tid : min(max(a.keep_idx[row * a.n_keep + tid], 0), PBK - 1);
     qtok[tid] = k >= 0 ? origin + koff[k] : -1;
+    qwin[tid] = (short)((k >= 0 && !g.dense && center_of(g, k) == k) ? window_of(g, k) : -1);
     if (k >= 0) keepflag[k] = 1;
   }
   __syncthreads();
-  int cpos = -1;  // position of the center among the retained rows (same in every thread)
-  if (!g.dense)
-    for (int q = 0; q < a.n_keep; ++q)
-      if (qtok[q] == origin + koff[g.center]) cpos = q;
 
-  // gradient of the fill copies: the dO rows of the pruned tokens, summed per channel; a
-  // thread adds its row group's tokens in ascending id, the groups are added in order below
+  // Gradient of the fill copies: per window, the dO rows of its pruned tokens summed per
+  // channel.  G row groups share a window: each adds every G-th token of the window in
+  // ascending id, then the groups' sums are added in order.
   if (!g.dense) {
-    float acc[8];
+    const int G = g.nwin >= RPP ? 1 : RPP / g.nwin;  // row groups per window
+    const int WB = g.nwin >= RPP ? RPP : g.nwin;     // windows per batch
+    for (int w0 = 0; w0 < g.nwin; w0 += WB) {
+      const int w = w0 + rg / G, sub = rg % G;
+      float acc[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int u = rg; u < PBK; u += RPP) {
-      if (keepflag[u]) continue;
-      const u32x4 pv = *reinterpret_cast<const u32x4*>(dOh + (int64_t)(origin + koff[u]) * D + 8 * c);
+      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+      if (rg < WB * G && w < g.nwin) {
+        for (int k = sub; k < g.Wk; k += G) {
+          const int u = wtok[w * g.Wk + k];
+          if (keepflag[u]) continue;
+          const u32x4 pv = *reinterpret_cast<const u32x4*>(dOh + (int64_t)(origin + koff[u]) * D + 8 * c);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc[2 * e] += __uint_as_float(pv[e] << 16);
-        acc[2 * e + 1] += __uint_as_float(pv[e] & 0xffff0000u);
+          for (int e = 0; e < 4; ++e) {
+            acc[2 * e] += __uint_as_float(pv[e] << 16);
+            acc[2 * e + 1] += __uint_as_float(pv[e] & 0xffff0000u);
+          }
+        }
       }
-    }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) fold[rg][8 * c + e] = acc[e];
+      for (int e = 0; e < 8; ++e) partial[rg * D + 8 * c + e] = acc[e];
+      __syncthreads();
+      for (int t = tid; t < WB * D; t += 256) {
+        const int wl = t / D, ch = t % D;
+        if (w0 + wl < g.nwin) {
+          float sum = 0.f;
+          for (int k = 0; k < G; ++k) sum += partial[(wl * G + k) * D + ch];
+          foldw[(w0 + wl) * D + ch] = sum;
+        }
+      }
+      __syncthreads();
+    }
   }
-  __syncthreads();
 
   for (int q = rg; q < R::NQ; q += RPP) {
     const int tok = qtok[q];
@@ -539,10 +571,10 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
         gf[2 * e] = __uint_as_float(gv[e] << 16);
         gf[2 * e + 1] = __uint_as_float(gv[e] & 0xffff0000u);
       }
-      if (q == cpos) {
-        for (int k = 0; k < RPP; ++k)
+      const int w = qwin[q];
+      if (w >= 0) {  // a window's critical token: its own dO plus its window's fill copies
 #pragma unroll
-          for (int e = 0; e < 8; ++e) gf[e] += fold[k][8 * c + e];
+        for (int e = 0; e < 8; ++e) gf[e] += foldw[w * D + 8 * c + e];
 #pragma unroll
         for (int e = 0; e < 4; ++e) gv[e] = pack_bf16(gf[2 * e], gf[2 * e + 1]);
       }
@@ -1097,7 +1129,8 @@ static int launch_bwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
   using R = BwdRec<D, NQT>;
   constexpr bool SPLITQ = NQT == 2;
   const int W = (g.N + 31) / 32;
-  if (a.stages & BSA_BWD_PRE) hipLaunchKernelGGL((bwd_pre_pipe_kernel<D, NQT>), dim3(g.rows), dim3(256), 0, st, g, a);
+  if (a.stages & BSA_BWD_PRE)  // LDS: per-row-group partial sums + per-window sums of the fill gradient
+    hipLaunchKernelGGL((bwd_pre_pipe_kernel<D, NQT>), dim3(g.rows), dim3(256), (size_t)(256 / (D / 8) + g.nwin) * D * 4, st, g, a);
   const size_t lds_q = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PG * W * 4;
   const size_t lds_kv = (size_t)4 * PBK * D * 2 + (size_t)DkvRing<NQT>::NB * R::BYTES + (size_t)2 * W * 4;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_pipe_kernel<D, SPLITQ, false>),
@@ -1145,6 +1178,8 @@ static int launch_fwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
   const int W = (g.N + 31) / 32;
   const size_t lds = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PG * W * 4;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ, false>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ, true>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
     return BSA_ERR_LAUNCH;
   const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense && a.fwd_ws != nullptr);
@@ -1152,8 +1187,9 @@ static int launch_fwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
   a.split_n = p.n;
   a.part = static_cast<float*>(a.fwd_ws);
   hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ, false>), dim3(p.grid), dim3(SPLITQ ? 512 : 256), lds, st, g, a);
-  if (p.units)
-    hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ, true>), dim3(p.units), dim3(SPLITQ ? 512 : 256), 0, st, g, a);
+  if (p.units)  // the combine launch needs LDS only for the parked critical-token rows
+    hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ, true>), dim3(p.units), dim3(SPLITQ ? 512 : 256),
+                       (size_t)PG * g.nwin * D * 2, st, g, a);
   return check_launch();
 }
 

@@ -16,7 +16,8 @@ struct Geom {
   int N;           // blocks per head
   int L;           // tokens per head
   int rows;        // B*H*N
-  int center;      // intra-block id of the critical token (Sec. 3.2.2)
+  int Wt, Wh, Ww;  // window of the critical-token mechanism (Sec. 3.2.2); the whole block when one center per block
+  int nwin, Wk;    // windows per block, tokens per window
   int dense;       // 1: tiles are runs of Bk consecutive raster tokens (dense baseline)
   uint32_t inv_Nw, inv_NwNh;  // floor(2^32 / x) + 1 (0 when x == 1): n / x == umulhi(n, inv) for n < 2^16
 };
@@ -53,6 +54,23 @@ __host__ __device__ inline int intra_offset(const Geom& g, int c) {
   return (ct * g.Hs + ch) * g.Ws + cw;
 }
 
+// Window (numbered raster-wise over the block's window grid) of intra-block token c.
+__host__ __device__ inline int window_of(const Geom& g, int c) {
+  if (g.nwin == 1) return 0;
+  const int cw = c % g.Cw, ch = (c / g.Cw) % g.Ch, ct = c / (g.Cw * g.Ch);
+  return ((ct / g.Wt) * (g.Ch / g.Wh) + ch / g.Wh) * (g.Cw / g.Ww) + cw / g.Ww;
+}
+
+// Intra-block id of the critical token of window w: local coordinate (Wt/2, Wh/2, Ww/2).
+__host__ __device__ inline int window_center(const Geom& g, int w) {
+  const int nw = g.Cw / g.Ww, nh = g.Ch / g.Wh;
+  const int c = w % nw, b = (w / nw) % nh, a = w / (nw * nh);
+  return ((a * g.Wt + g.Wt / 2) * g.Ch + b * g.Wh + g.Wh / 2) * g.Cw + c * g.Ww + g.Ww / 2;
+}
+
+// Critical token of the window that holds intra-block token c.
+__host__ __device__ inline int center_of(const Geom& g, int c) { return window_center(g, window_of(g, c)); }
+
 int make_geom(const bsa_shape_t* s, Geom* g);  // validates; returns bsa_status
 
 inline int check_launch() {
@@ -77,7 +95,7 @@ template <> __device__ inline void store_f32<uint16_t>(uint16_t* p, float v) { *
 
 // ---- entry points implemented per translation unit (all enqueue on `st`) ----
 int launch_pool(const Geom& g, int dtype, const void* X, double* Xbar, hipStream_t st);
-int launch_prune(const Geom& g, int dtype, const void* Q, int n_keep, int32_t* keep_idx, hipStream_t st);
+int launch_prune(const Geom& g, int dtype, const void* Q, int window_quota, int32_t* keep_idx, hipStream_t st);
 size_t select_workspace_bytes(const Geom& g);
 int launch_select(const Geom& g, const double* Qbar, const double* Kbar, double threshold,
                   double score_scale, int32_t* q2k_ptr, int32_t* q2k_idx, int32_t* k2q_ptr,

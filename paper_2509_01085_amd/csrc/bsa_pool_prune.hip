@@ -90,8 +90,10 @@ __global__ __launch_bounds__(64 * kWaves) void pool_kernel(Geom g, const uint8_t
 // ------------------------------------------------------------------------------ pruning
 // Lane t owns token t of the block (Bk > 64: several passes).  The token rows pass through a
 // per-wavefront LDS tile in groups of up to 8 sixteen-byte chunks: loaded row-contiguous
-// (coalesced), read back one row per lane; the dot product with the center and the squared
-// norm accumulate over the channels in ascending order across the groups.
+// (coalesced), read back one row per lane; the dot product with the center of the token's
+// window and the two squared norms accumulate over the channels in ascending order across the
+// groups.  Ranking and quota are per window (Sec. 3.2.2, "Critical Token"); one window per
+// block is the single-center method.
 constexpr int kGroup = 8;                          // chunks of a row staged at a time
 constexpr int kRowStride = kGroup * 16 + 16;       // LDS bytes per staged row (padded: lanes 16 apart share banks, the b128 minimum)
 constexpr int kTileBytes = 64 * kRowStride;
@@ -103,50 +105,35 @@ __device__ inline void wave_lds_sync() {  // LDS written by other lanes of this 
 }
 
 template <int ES>
-__global__ __launch_bounds__(64 * kWaves) void prune_kernel(Geom g, const uint8_t* Q, int n_keep,
+__global__ __launch_bounds__(64 * kWaves) void prune_kernel(Geom g, const uint8_t* Q, int kw,
                                                            int32_t* keep_idx) {
   __shared__ __align__(16) uint8_t tiles[kWaves][kTileBytes];
-  __shared__ __align__(16) uint8_t crow[kWaves][256 * 4];  // the center token's row
   __shared__ double cosv[kWaves][256];
   __shared__ int koff[256];
+  __shared__ short wid[256];   // window of every intra-block token
+  __shared__ short wcen[256];  // critical token of that window (intra-block id)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int t = threadIdx.x; t < g.Bk; t += 64 * kWaves) koff[t] = intra_offset(g, t);
+  for (int t = threadIdx.x; t < g.Bk; t += 64 * kWaves) {
+    koff[t] = intra_offset(g, t);
+    const int w = window_of(g, t);
+    wid[t] = (short)w;
+    wcen[t] = (short)window_center(g, w);
+  }
   __syncthreads();  // the only workgroup barrier; wavefronts are independent from here on
   const int64_t row = (int64_t)blockIdx.x * kWaves + wave;
   if (row >= g.rows) return;
   const int64_t bh = row / g.N;
   const int i = (int)(row % g.N);
   const int row_bytes = g.d * ES, cpr = row_bytes / 16;
+  const int n_keep = kw * g.nwin;
   const uint8_t* base = Q + (bh * g.L + block_origin(g, i)) * (int64_t)row_bytes;
   uint8_t* tile = tiles[wave];
-  uint8_t* cr = crow[wave];
-
-  for (int q = lane; q < cpr; q += 64)
-    *reinterpret_cast<uint4*>(cr + 16 * q) = *reinterpret_cast<const uint4*>(base + (int64_t)koff[g.center] * row_bytes + 16 * q);
-  wave_lds_sync();
-  constexpr int EPC = 16 / ES;  // channels per chunk
-  double nc2 = 0.0;             // |q_c|^2, same channel order in every lane
-  for (int q = 0; q < cpr; ++q) {
-    const uint4 cv = *reinterpret_cast<const uint4*>(cr + 16 * q);
-    const uint32_t cw[4] = {cv.x, cv.y, cv.z, cv.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      if (ES == 4) {
-        const double x = (double)__uint_as_float(cw[e]);
-        nc2 = fma(x, x, nc2);
-      } else {
-        double lo, hi;
-        unpack<ES>(cw[e], lo, hi);
-        nc2 = fma(lo, lo, nc2);
-        nc2 = fma(hi, hi, nc2);
-      }
-    }
-  }
-  (void)EPC;
 
   for (int t0 = 0; t0 < g.Bk; t0 += 64) {
     const int nt = min(64, g.Bk - t0);
-    double dot = 0.0, na2 = 0.0;
+    const int cen = wcen[min(t0 + lane, g.Bk - 1)];  // this lane's window center
+    const bool cen_staged = cen >= t0 && cen < t0 + nt;  // its row is part of this pass's tile
+    double dot = 0.0, na2 = 0.0, nc2 = 0.0;  // <q, q_c>, |q|^2, |q_c|^2: channels ascending
     for (int q0 = 0; q0 < cpr; q0 += kGroup) {
       const int nq = min(kGroup, cpr - q0);
       wave_lds_sync();  // everyone is done reading the previous group
@@ -167,22 +154,27 @@ __global__ __launch_bounds__(64 * kWaves) void prune_kernel(Geom g, const uint8_
       if (lane < nt) {
         for (int q = 0; q < nq; ++q) {
           const uint4 xv = *reinterpret_cast<const uint4*>(tile + lane * kRowStride + 16 * q);
-          const uint4 cv = *reinterpret_cast<const uint4*>(cr + 16 * (q0 + q));
+          const uint4 cv = cen_staged
+                               ? *reinterpret_cast<const uint4*>(tile + (cen - t0) * kRowStride + 16 * q)
+                               : *reinterpret_cast<const uint4*>(base + (int64_t)koff[cen] * row_bytes + 16 * (q0 + q));
           const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w}, cw[4] = {cv.x, cv.y, cv.z, cv.w};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             if (ES == 4) {
-              const double x = (double)__uint_as_float(xw[e]);
-              dot = fma(x, (double)__uint_as_float(cw[e]), dot);
+              const double x = (double)__uint_as_float(xw[e]), c = (double)__uint_as_float(cw[e]);
+              dot = fma(x, c, dot);
               na2 = fma(x, x, na2);
+              nc2 = fma(c, c, nc2);
             } else {
               double xl, xh, cl, ch;
               unpack<ES>(xw[e], xl, xh);
               unpack<ES>(cw[e], cl, ch);
               dot = fma(xl, cl, dot);
               na2 = fma(xl, xl, na2);
+              nc2 = fma(cl, cl, nc2);
               dot = fma(xh, ch, dot);
               na2 = fma(xh, xh, na2);
+              nc2 = fma(ch, ch, nc2);
             }
           }
         }
@@ -200,16 +192,17 @@ __global__ __launch_bounds__(64 * kWaves) void prune_kernel(Geom g, const uint8_
     const int t = t0 + lane;
     bool keep = false;
     if (t < g.Bk) {
-      if (t == g.center) {
+      const int w = wid[t], cen = wcen[t];
+      if (t == cen) {
         keep = true;
       } else {
         const double ct = cosv[wave][t];
-        int rank = 0;  // tokens (center excluded) ordered before t: smaller cosine, then smaller id
+        int rank = 0;  // tokens of the window (center excluded) ordered before t: smaller cosine, then smaller id
         for (int u = 0; u < g.Bk; ++u) {
           const double cu = cosv[wave][u];
-          rank += (u != g.center && u != t) && ((cu < ct) || (cu == ct && u < t));
+          rank += (wid[u] == w && u != cen && u != t) && ((cu < ct) || (cu == ct && u < t));
         }
-        keep = rank < n_keep - 1;
+        keep = rank < kw - 1;
       }
     }
     const unsigned long long m = __ballot(keep);
@@ -228,13 +221,13 @@ int launch_pool(const Geom& g, int dtype, const void* X, double* Xbar, hipStream
   return check_launch();
 }
 
-int launch_prune(const Geom& g, int dtype, const void* Q, int n_keep, int32_t* keep_idx, hipStream_t st) {
+int launch_prune(const Geom& g, int dtype, const void* Q, int window_quota, int32_t* keep_idx, hipStream_t st) {
   const uint8_t* q = static_cast<const uint8_t*>(Q);
   const dim3 grid((g.rows + kWaves - 1) / kWaves), block(64 * kWaves);
   if (dtype == BSA_F32)
-    hipLaunchKernelGGL(prune_kernel<4>, grid, block, 0, st, g, q, n_keep, keep_idx);
+    hipLaunchKernelGGL(prune_kernel<4>, grid, block, 0, st, g, q, window_quota, keep_idx);
   else
-    hipLaunchKernelGGL(prune_kernel<2>, grid, block, 0, st, g, q, n_keep, keep_idx);
+    hipLaunchKernelGGL(prune_kernel<2>, grid, block, 0, st, g, q, window_quota, keep_idx);
   return check_launch();
 }
 

@@ -35,11 +35,11 @@ def progress(msg: str) -> None:
 
 
 def shape_of(wl: Workload) -> B.Shape:
-    return B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16)
+    return B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16, *wl.window)
 
 
 def part_of(wl: Workload) -> o.Partition:
-    return o.Partition(*wl.grid, *wl.block)
+    return o.Partition(*wl.grid, *wl.block, *wl.window)
 
 
 def device_inputs(wl: Workload, names=("Q", "K", "V", "dO"), heads: Optional[Iterable[int]] = None) -> Dict[str, torch.Tensor]:
@@ -136,7 +136,7 @@ def rounding_bounds(xi: dict, part: o.Partition, ix, sm_scale: float, q_blocks=N
         dS = P * (g @ v.T - (g * out).sum(axis=1, keepdims=True))
         ddS = u * (P * (np.abs(g) @ np.abs(v).T) + np.abs(dS))
         eO = u * (P @ np.abs(v))
-        cpos = int(np.nonzero(ix.keep_idx[i] == part.center)[0][0])
+        cpos = np.searchsorted(ix.keep_idx[i], part.center_of())  # each token's window center among the retained rows
         E["O"][tok[i]] = eO[cpos]
         E["O"][rows] = eO
         E["dQ"][rows] = sm_scale * (ddS @ np.abs(k))

@@ -75,6 +75,11 @@ def test_null_range_capacity_workspace_errors_come_before_any_launch():
     assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 0, 0.125, p, p, None, 0, None) == -3
     assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 33, 0.125, p, p, None, 0, None) == -3
     assert lib.bsa_attn_fwd(s, p, p, None, p, p, p, 16, 0.125, p, p, None, 0, None) == -1
+    # windows of the critical-token mechanism must divide the block; the quota is per window
+    wshape = lambda *w: C.byref(B.Shape(1, 2, 4, 8, 8, 2, 4, 4, 64, B.F32, *w).c())
+    assert lib.bsa_n_keep(wshape(1, 2, 2), 0.5) == 8 * 2 and lib.bsa_n_keep(wshape(2, 4, 4), 0.5) == 16
+    assert lib.bsa_n_keep(wshape(1, 2, 2), 0.3) == 8 * 2  # ceil(0.3 * 4) per window
+    assert lib.bsa_n_keep(wshape(1, 3, 2), 0.5) == -2 and lib.bsa_n_keep(wshape(-1, 2, 2), 0.5) == -2
     assert B.fwd_workspace_bytes(GOOD, 16) == 0  # fp32 shapes run the plain kernels: nothing to split
     big = B.Shape(1, 12, 20, 32, 52, 4, 4, 4, 128, B.BF16)  # a short launch on the MFMA path: the tail is split
     fws = B.fwd_workspace_bytes(big, 32)

@@ -20,6 +20,7 @@ pytestmark = pytest.mark.gpu
 # workload -> (heads checked, query blocks sampled per head, KV blocks sampled per head)
 PLAN = {
     "wan1p3b": ((0, 7, 11), 6, 2),
+    "wan1p3b_win": ((4,), 4, 1),
     "hd720p": ((3, 39), 4, 1),
     "long": ((5,), 4, 1),
 }

@@ -41,6 +41,14 @@ CASES = {
     # last query-block group ragged, two wavefronts per query block)
     "split_tail": Workload("split_tail", 1, 2, 128, "bf16", (16, 16, 24), (4, 4, 4), threshold=0.7),
     "split_ragged": Workload("split_ragged", 1, 5, 64, "bf16", (12, 12, 20), (4, 4, 4), threshold=0.7, keep_ratio=0.75),
+    # window-based critical tokens (Sec. 3.2.2): the paper's (2,2,2) windows in 4x4x4 blocks on the
+    # MFMA path, small windows on the fp32 path, and windows that do not tile the block into a
+    # power-of-two count (3 windows of a 3x2x4 block)
+    "win_tiny": WORKLOADS["tiny"].replace(window=(1, 2, 2), threshold=0.6, seed=2),
+    "win_wan": Workload("win_wan", 1, 2, 128, "bf16", (8, 8, 12), (4, 4, 4), threshold=0.6, window=(2, 2, 2)),
+    "win_wan_r75": Workload("win_wan_r75", 1, 2, 64, "bf16", (8, 8, 12), (4, 4, 4), threshold=0.7, keep_ratio=0.75, window=(2, 4, 4)),
+    "win_split": Workload("win_split", 1, 2, 128, "bf16", (16, 16, 24), (4, 4, 4), threshold=0.7, window=(2, 2, 2), seed=3),
+    "win_ragged": Workload("win_ragged", 1, 2, 72, "fp32", (6, 6, 8), (3, 2, 4), threshold=0.7, keep_ratio=0.5, window=(1, 2, 4)),
     # threshold 1: every block selected
     "p_one": Workload("p_one", 1, 1, 64, "bf16", (4, 8, 8), (2, 4, 4), threshold=1.0, keep_ratio=0.5),
 }
@@ -122,17 +130,18 @@ def test_backward_matches_oracle(name):
             assert U.parity_excess(got, ref, r["wl"].dtype, A.get(name)) < tol, (name, U.rel_err(got, ref))
 
 
-@pytest.mark.parametrize("name", ["tiny_p60", "mini_wan", "ragged_bf16"])
+@pytest.mark.parametrize("name", ["tiny_p60", "mini_wan", "ragged_bf16", "win_tiny", "win_wan", "win_ragged"])
 def test_fill_and_zero_rows_are_exact(name):
     r = run_case(name)
     part, tok = r["part"], r["part"].block_tokens()
+    cof = part.center_of()
     for b, h in heads(r):
         keep = r["ref"][b, h][0].keep_idx
         O, LSE, dQ = (r[k][b, h].float().cpu().numpy() for k in ("O", "LSE", "dQ"))
         for i in range(part.N):
             pruned = np.setdiff1d(np.arange(part.Bk), keep[i])
-            c = tok[i, part.center]
-            assert np.array_equal(O[tok[i, pruned]], np.tile(O[c], (len(pruned), 1)))
+            c = tok[i, cof[pruned]]  # each pruned token's window center
+            assert np.array_equal(O[tok[i, pruned]], O[c])
             assert np.all(LSE[tok[i, pruned]] == LSE[c])
             assert not dQ[tok[i, pruned]].any()
 
