@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="the sparsity sweep instead of the single benchmark: sigma x threshold x keep_ratio on the "
                          "workload's shape, one JSON line per point (seed = point index)")
+    ap.add_argument("--length-sweep", action="store_true",
+                    help="speedup over the in-repo dense kernel versus sequence length (forward only and forward + "
+                         "backward), one JSON line per length, at the paper's token counts from 23K to 153K")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain elementwise copy of this many MiB (read + write that much each), "
                          "the known-traffic dispatch that hardware-counter readings are scaled by")
@@ -156,6 +159,59 @@ def sweep(args, torch, B):
                 del x, Q, K, V, dO, O, dQ, dK, dV, lists, ws, fws
 
 
+# Latent grids for the paper's sequence lengths (Table 1 and the speedup-versus-length figure:
+# 23,296 ... 153,600 tokens).  The paper does not print the grids: the two end points follow
+# from its video sizes (61x448x832 and 157x768x1280 with a 4x8x8 VAE and 1x2x2 patches); the
+# three in between are grids of about the quoted lengths that 4x4x4 blocks divide.
+LENGTH_GRIDS = ((16, 28, 52), (16, 44, 64), (24, 44, 56), (36, 48, 68), (40, 48, 80))
+
+
+def length_sweep(args, torch, B):
+    from bsa_workloads import WORKLOADS
+
+    dev = torch.device("cuda:0")
+    base = WORKLOADS["wan1p3b_win"]  # the paper's defaults: 4x4x4 blocks, (2,2,2) windows, r = 0.5
+    for grid in LENGTH_GRIDS:
+        for p in (0.9, 0.6):
+            wl = base.replace(grid=grid, threshold=p)
+            shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.BF16, *wl.window)
+            x = make_inputs(wl, torch)
+            Q, K, V, dO = x["Q"], x["K"], x["V"], x["dO"]
+            nk = B.n_keep(shp, wl.keep_ratio)
+            lists = B.alloc_kv_lists(shp, dev)
+            O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+            LSE = torch.empty((wl.B, wl.H, wl.L), dtype=torch.float32, device=dev)
+            ws = torch.empty(max(1, B.bwd_workspace_bytes(shp, nk), B.dense_bwd_workspace_bytes(shp)), dtype=torch.uint8, device=dev)
+            fws = torch.empty(max(1, B.fwd_workspace_bytes(shp, nk)), dtype=torch.uint8, device=dev)
+            state = {}
+
+            def fwd():  # everything a forward pass needs: indices and attention
+                B.select_kv(shp, B.pool_blocks(shp, Q), B.pool_blocks(shp, K), p, out=lists)
+                state["keep"] = B.prune_q(shp, Q, wl.keep_ratio)
+                B.attn_fwd(shp, Q, K, V, lists, state["keep"], O=O, LSE=LSE, workspace=fws)
+
+            def bwd():
+                B.attn_bwd(shp, Q, K, V, O, LSE, dO, lists, state["keep"], dQ=dQ, dK=dK, dV=dV, workspace=ws)
+
+            dfw = lambda: B.dense_attn_fwd(shp, Q, K, V, O=O, LSE=LSE)
+            dbw = lambda: B.dense_attn_bwd(shp, Q, K, V, O, LSE, dO, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+            fwd(); bwd()
+            t_f, t_b = timed(torch, fwd, args.steps), timed(torch, bwd, args.steps)
+            nnz = int(lists.nnz.item())
+            dfw(); dbw()
+            n = max(1, min(2, args.steps))
+            td_f, td_b = timed(torch, dfw, n), timed(torch, dbw, n)
+            f = nnz / (shp.rows * shp.N)
+            print(json.dumps({
+                "tokens": wl.L, "grid": list(grid), "threshold": p, "keep_ratio": wl.keep_ratio, "window": list(wl.window),
+                "selected_block_fraction": f, "sparsity": 1.0 - (nk / shp.Bk) * f,
+                "bsa_fwd_ms": t_f, "bsa_bwd_ms": t_b, "dense_fwd_ms": td_f, "dense_bwd_ms": td_b,
+                "speedup_fwd": td_f / t_f, "speedup_fwd_bwd": (td_f + td_b) / (t_f + t_b),
+                "ideal_speedup": 1.0 / ((nk / shp.Bk) * f),
+            }), flush=True)
+            del x, Q, K, V, dO, O, dQ, dK, dV, lists, ws, fws
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -166,9 +222,9 @@ def main():
     from bsa_workloads import WORKLOADS
     from paper_2509_01085_amd import binding as B
 
-    if args.sweep:
+    if args.sweep or args.length_sweep:
         torch.cuda.set_device(0)
-        sweep(args, torch, B)
+        (sweep if args.sweep else length_sweep)(args, torch, B)
         return
     wl = WORKLOADS[args.workload]
     over = {k: v for k, v in (("sigma", args.sigma), ("threshold", args.threshold), ("keep_ratio", args.keep_ratio)) if v is not None}

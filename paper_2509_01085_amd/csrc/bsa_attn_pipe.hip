@@ -43,20 +43,6 @@ __device__ inline int xcd_remap8(int n, int total) {
 // and a combine launch merges their partial results.
 constexpr int kCUs = 256;  // compute units of the MI355X
 
-#ifdef BSA_TRACE  // development aid: per-workgroup start/end times of the forward launch
-__device__ unsigned long long g_trace[4 * 65536];
-#define BSA_TRACE_BEGIN() const unsigned long long trace_t0 = wall_clock64()
-#define BSA_TRACE_END()                                                                       \
-  if (threadIdx.x == 0 && blockIdx.x < 65536) {                                               \
-    g_trace[4 * blockIdx.x] = trace_t0;                                                       \
-    g_trace[4 * blockIdx.x + 1] = wall_clock64();                                             \
-    g_trace[4 * blockIdx.x + 2] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));       \
-    g_trace[4 * blockIdx.x + 3] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));      \
-  }
-#else
-#define BSA_TRACE_BEGIN()
-#define BSA_TRACE_END()
-#endif
 
 struct SplitPlan {
   int S, n;   // segments per split unit; split units per XCD (0: no splitting)
@@ -156,7 +142,6 @@ struct Walk4 {
 // a split unit and finish it.  Both end in the same epilogue.
 template <int D, bool SPLITQ, bool COMBINE>
 __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g, AttnArgs a) {
-  BSA_TRACE_BEGIN();
   constexpr int NT = SPLITQ ? 512 : 256;  // threads
   constexpr int NB = SPLITQ ? 4 : 2;      // LDS ring depth (tiles)
   constexpr int RB = D * 2;               // bytes per tile row
@@ -276,13 +261,16 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
     for (int sg = 0; sg < it.nseg; ++sg) m = fmaxf(m, part[(int64_t)sg * NW * NREG * 64 + (NREG - 2) * 64]);
     for (int sg = 0; sg < it.nseg; ++sg) {
       const float* ps = part + (int64_t)sg * NW * NREG * 64;
-      const float ms = ps[(NREG - 2) * 64];
+      float v[NREG];  // the segment's values first, all loads in flight together
+#pragma unroll
+      for (int k = 0; k < NREG; ++k) v[k] = __builtin_nontemporal_load(ps + k * 64);
+      const float ms = v[NREG - 2];
       const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - m);
-      l += w * ps[(NREG - 1) * 64];
+      l += w * v[NREG - 1];
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[dt][r] += w * ps[(dt * 16 + r) * 64];
+        for (int r = 0; r < 16; ++r) o[dt][r] += w * v[dt * 16 + r];
     }
   }
   Walk4 walk(masks, W, qb);  // runs NB-1 tiles ahead of the multiplication; `pending` remembers
@@ -399,7 +387,6 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
       for (int r = 0; r < 16; ++r) ps[(dt * 16 + r) * 64] = o[dt][r];
     ps[(NREG - 2) * 64] = m;
     ps[(NREG - 1) * 64] = l;
-    BSA_TRACE_END();
     return;
   }
   // epilogue: normalise, store the retained rows, park the rows of the windows' critical tokens
@@ -445,7 +432,6 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
       Lh[tok] = cen_lse[qb][win];
     }
   }
-  if (!COMBINE) { BSA_TRACE_END(); }
 }
 
 // =====================================================================================
@@ -719,10 +705,13 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
   if (COMBINE) {
     for (int sg = 0; sg < it.nseg; ++sg) {
       const float* ps = part + (int64_t)sg * NW * NREG * 64;
+      float v[NREG];  // all loads of the segment in flight together
+#pragma unroll
+      for (int k = 0; k < NREG; ++k) v[k] = __builtin_nontemporal_load(ps + k * 64);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) dq[dt][r] += ps[(dt * 16 + r) * 64];
+        for (int r = 0; r < 16; ++r) dq[dt][r] += v[dt * 16 + r];
     }
   }
   Walk4 walk(masks, W, qb);
@@ -1200,9 +1189,3 @@ int launch_fwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st) {
 }
 
 }  // namespace bsa
-
-#ifdef BSA_TRACE
-extern "C" int bsa_debug_trace(void* host_dst, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(bsa::g_trace), bytes);
-}
-#endif
