@@ -31,8 +31,8 @@ PEAK_HBM_GBS = 8000.0
 # Hardware counters cannot be read from inside this process, so the figure is carried here.
 MEASURED_TRAFFIC_BYTES = {
     ("wan1p3b", "bwd_dkv_pipe_kernel"): 3.45e9,
-    ("wan1p3b", "bwd_dq_pipe_kernel"): 10.02e9,
-    ("wan1p3b", "fwd_pipe_kernel"): 9.07e9,
+    ("wan1p3b", "bwd_dq_pipe_kernel"): 10.53e9,
+    ("wan1p3b", "fwd_pipe_kernel"): 9.73e9,
 }
 
 
