@@ -10,6 +10,10 @@ Passages followed (paper section / equation):
   * token <-> grid index map and block partition ....... Sec. 3.1, Sec. 3.2.1
   * block-level representations and inter-block scores .. Sec. 3.2.3
   * minimal cumulative-mass KV-block set ................ Sec. 3.2.3, Eq. 4
+  * statistical dynamic threshold (candidate filter) .... Sec. 3.2.3, Eq. 3  (PARITY UNPINNED:
+    the equation is ambiguous about U, the std divisor, what p thresholds and how it
+    combines with Eq. 4; the reading taken is in select_row's docstring and the design
+    notes; the arithmetic of that reading is pinned, the reading itself cannot be)
   * query pruning by cosine similarity to the center .... Sec. 3.2.2, Eq. 2
   * window-based critical tokens ....................... Sec. 3.2.2 ("Critical Token")
   * token filling ...................................... Sec. 3.2.2 ("Token Filling")
@@ -218,12 +222,41 @@ class RowSelection:
     margin: float  # distance of the deciding comparisons from equality, relative to Z
 
 
-def select_row(s: np.ndarray, p: float) -> RowSelection:
+def stat_quantile(k: int, n: int) -> float:
+    """U(1 - k/n) of Eq. 3 with U read as the quantile function of the standard normal
+    distribution: the z for which about k of n normally distributed scores exceed
+    mean + z * std.  k = n gives -inf (no score is excluded)."""
+    if not (1 <= k <= n):
+        raise ValueError("Eq. 3 needs 1 <= k <= n")
+    if k == n:
+        return float("-inf")
+    from statistics import NormalDist
+
+    return NormalDist().inv_cdf(1.0 - k / n)
+
+
+def stat_threshold(s: np.ndarray, z: float) -> float:
+    """Eq. 3: mean(s) + std(s) * z, std with the n-1 divisor (0 for a single score)."""
+    s = np.asarray(s, dtype=np.float64)
+    if z == float("-inf"):
+        return float("-inf")
+    std = float(np.std(s, ddof=1)) if s.shape[0] > 1 else 0.0
+    return float(np.mean(s)) + std * float(z)
+
+
+def select_row(s: np.ndarray, p: float, z: Optional[float] = None) -> RowSelection:
     """Minimal prefix, in descending score order, with cumulative mass >= p.
 
     Order: score descending, ties by lower block id.  Mass is accumulated in
     that order; the test is c_k >= p * Z with Z the total of the same
-    accumulation.  p >= 1 selects every block."""
+    accumulation.  p >= 1 selects every block.
+
+    With `z` (Eq. 3, statistical dynamic threshold) only the blocks whose score
+    reaches tau = mean(s) + std(s) * z are candidates: the prefix is cut to the
+    candidates (they are themselves a prefix of the order); if none qualifies the
+    single best block is kept.  The softmax of Eq. 4 stays normalised over all
+    blocks, as printed.  The margin then also covers the comparisons with tau,
+    relative to |tau| + std."""
     if not (0.0 < p <= 1.0):
         raise ValueError("mass threshold p must lie in (0, 1]")
     s = np.asarray(s, dtype=np.float64)
@@ -233,23 +266,31 @@ def select_row(s: np.ndarray, p: float) -> RowSelection:
     c = np.cumsum(e)  # sequential accumulation in sorted order
     Z = c[-1]
     if p >= 1.0:
-        return RowSelection(np.arange(n, dtype=np.int32), n, float("inf"))
-    target = np.float64(p) * Z
-    k = int(np.argmax(c >= target)) + 1  # first k with c_k >= p Z  (c_n = Z >= pZ)
-    margin = (c[k - 1] - target) / Z
-    if k >= 2:
-        margin = min(margin, (target - c[k - 2]) / Z)
+        k, margin = n, float("inf")
+    else:
+        target = np.float64(p) * Z
+        k = int(np.argmax(c >= target)) + 1  # first k with c_k >= p Z  (c_n = Z >= pZ)
+        margin = (c[k - 1] - target) / Z
+        if k >= 2:
+            margin = min(margin, (target - c[k - 2]) / Z)
+    if z is not None and z != float("-inf"):
+        tau = stat_threshold(s, z)
+        cand = int(np.count_nonzero(s >= tau))
+        k = min(k, max(cand, 1))
+        std = float(np.std(s, ddof=1)) if n > 1 else 0.0
+        margin = min(float(margin), float(np.abs(s - tau).min() / (abs(tau) + std + 1e-300)))
     return RowSelection(np.sort(order[:k]).astype(np.int32), k, float(margin))
 
 
-def select_kv(scores: np.ndarray, p: float) -> Tuple[np.ndarray, np.ndarray, float]:
-    """CSR (q2k_ptr[N+1], q2k_idx[nnz]) of Eq. 4 for one head, plus the smallest margin."""
+def select_kv(scores: np.ndarray, p: float, z: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray, float]:
+    """CSR (q2k_ptr[N+1], q2k_idx[nnz]) of Eq. 4 (optionally behind Eq. 3's candidate
+    filter) for one head, plus the smallest margin."""
     n_rows = scores.shape[0]
     ptr = np.zeros(n_rows + 1, dtype=np.int32)
     cols: List[np.ndarray] = []
     margin = float("inf")
     for i in range(n_rows):
-        sel = select_row(scores[i], p)
+        sel = select_row(scores[i], p, z)
         cols.append(sel.idx)
         ptr[i + 1] = ptr[i] + sel.k
         margin = min(margin, sel.margin)
@@ -488,13 +529,13 @@ class HeadResult:
 
 
 def bsa_indices(Q, K, part: Partition, threshold: float, keep_ratio: float,
-                score_scale: Optional[float] = None) -> HeadResult:
-    """Pool -> block scores -> Eq. 4 selection, and Eq. 2 pruning, for one head."""
+                score_scale: Optional[float] = None, stat_z: Optional[float] = None) -> HeadResult:
+    """Pool -> block scores -> (Eq. 3 filter ->) Eq. 4 selection, and Eq. 2 pruning, for one head."""
     d = Q.shape[1]
     score_scale = 1.0 / sqrt(d) if score_scale is None else score_scale
     Qbar = pool_blocks(Q, part)
     Kbar = pool_blocks(K, part)
-    ptr, idx, margin = select_kv(block_scores(Qbar, Kbar, score_scale), threshold)
+    ptr, idx, margin = select_kv(block_scores(Qbar, Kbar, score_scale), threshold, stat_z)
     tptr, tidx = transpose_csr(ptr, idx, part.N)
     keep, gap = prune_q(Q, part, keep_ratio)
     return HeadResult(Qbar, Kbar, ptr, idx, tptr, tidx, keep, margin, gap)

@@ -1,4 +1,4 @@
-// Sparse-KV selection (Sec. 3.2.3, Eq. 4): block logits -> per-row descending sort ->
+// Sparse-KV selection (Sec. 3.2.3, Eq. 4): block logits -> per-row order (score descending) ->
 // cumulative softmax mass -> minimal prefix reaching the threshold -> CSR block lists
 // (the paper's q2k_num / q2k_index of Sec. 3.3) plus the transposed lists that give every
 // KV block a single owner in the backward pass.

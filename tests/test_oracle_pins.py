@@ -478,3 +478,46 @@ def test_window_fwd_bwd_against_autograd_of_masked_dense_form(p, r):
                 assert np.array_equal(O[tok[i, c]], O[_window_center_by_coordinates(part, tok[i, c])])
                 assert not dQ[tok[i, c]].any()
     assert pruned_any
+
+
+# ----------------------------- Eq. 3: statistical dynamic threshold (reading; arithmetic pinned)
+def test_stat_quantile_selects_about_k_of_n_normal_scores():
+    """The paper's stated purpose of Eq. 3: the threshold is such that k key samples pass."""
+    from statistics import NormalDist
+
+    n = 2000
+    s = np.array([NormalDist(mu=1.5, sigma=0.7).inv_cdf((j + 0.5) / n) for j in range(n)])  # an exactly normal sample
+    for k in (20, 200, 1000, 1800):
+        tau = o.stat_threshold(s, o.stat_quantile(k, n))
+        assert abs(int((s >= tau).sum()) - k) <= 2
+    assert o.stat_quantile(n, n) == float("-inf")
+    assert abs(o.stat_quantile(n // 2, n)) < 1e-12  # the median: z = 0
+    with pytest.raises(ValueError):
+        o.stat_quantile(0, 10)
+
+
+def test_stat_threshold_hand_example_and_invariances():
+    s = np.array([0.0, 1.0, 2.0, 3.0, 4.0])
+    assert o.stat_threshold(s, 0.0) == 2.0
+    assert abs(o.stat_threshold(s, 1.0) - (2.0 + sqrt(2.5))) < 1e-15  # n-1 divisor: var = 10/4
+    sel = o.select_row(s, 1.0, 0.0)  # mass threshold off: exactly the candidates {2,3,4}
+    assert sel.idx.tolist() == [2, 3, 4]
+    assert o.select_row(s, 1.0, 5.0).idx.tolist() == [4]  # no candidate: the best block alone
+    # z = -inf (k = n) and z = None are plain Eq. 4
+    rng = np.random.default_rng(11)
+    r = rng.normal(size=40) * 2
+    for p in (0.5, 0.9):
+        a, b, c = o.select_row(r, p), o.select_row(r, p, float("-inf")), o.select_row(r, p, -50.0)
+        assert a.idx.tolist() == b.idx.tolist() == c.idx.tolist()
+    # the candidate set is invariant under s -> a s + b (a > 0)
+    z = 0.3
+    base = set(o.select_row(r, 1.0, z).idx.tolist())
+    assert base == set(o.select_row(3.0 * r - 7.0, 1.0, z).idx.tolist())
+    # the result is the intersection of Eq. 4's prefix with the candidates, never empty
+    for p in (0.3, 0.7, 0.95):
+        for z in (-1.0, 0.0, 1.0, 2.5):
+            full = o.select_row(r, p).idx.tolist()
+            cand = [j for j in range(40) if r[j] >= o.stat_threshold(r, z)]
+            got = o.select_row(r, p, z).idx.tolist()
+            want = sorted(set(full) & set(cand)) or [int(np.argmax(r))]
+            assert got == want
