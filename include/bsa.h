@@ -100,6 +100,22 @@ int bsa_select_kv(const bsa_shape_t* shape, const double* Qbar, const double* Kb
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same selection behind the statistical dynamic threshold of Sec. 3.2.3, Eq. 3: per row,
+ * only the blocks whose logit reaches tau = mean(s_i.) + std(s_i.) * stat_z (std with the
+ * n-1 divisor) are candidates, and the minimal prefix of Eq. 4 is cut to them; a row with no
+ * candidate keeps its best block.  stat_z is the standard-normal quantile U(1 - k/n) for k
+ * desired blocks of n, computed by the caller; -inf disables the filter, NaN is
+ * BSA_ERR_RANGE.  The softmax mass of Eq. 4 stays normalised over all N blocks.
+ * (The paper's equation leaves U, the divisor and the composition with Eq. 4 open: this is
+ * one documented reading.)  All other arguments as bsa_select_kv.
+ */
+int bsa_select_kv_stat(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
+                       double threshold, double stat_z, double score_scale,
+                       int32_t* q2k_ptr, int32_t* q2k_idx, int64_t idx_capacity,
+                       int32_t* k2q_ptr, int32_t* k2q_idx, int64_t* nnz_dev,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Sparse Query (Sec. 3.2.2, Eq. 2, and "Critical Token").  Per window of every block (the
  * whole block when shape.Wt/Wh/Ww are 0): cosine similarity (fp64) of every token of the
  * window to the window's critical token, local coordinate (Wt/2, Wh/2, Ww/2); the critical

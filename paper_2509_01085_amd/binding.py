@@ -21,7 +21,7 @@ _LIB_PATH = os.environ.get("BSA_LIB") or os.path.join(os.path.dirname(os.path.ab
 F32, BF16 = 0, 1
 EXPORTS = (
     "bsa_strerror", "bsa_n_keep", "bsa_pool_blocks", "bsa_select_workspace_bytes", "bsa_select_kv",
-    "bsa_prune_q", "bsa_fwd_workspace_bytes", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd", "bsa_attn_bwd_stages",
+    "bsa_select_kv_stat", "bsa_prune_q", "bsa_fwd_workspace_bytes", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd", "bsa_attn_bwd_stages",
     "bsa_dense_bwd_workspace_bytes", "bsa_dense_attn_fwd", "bsa_dense_attn_bwd",
 )
 
@@ -54,6 +54,8 @@ def lib() -> C.CDLL:
         L.bsa_select_workspace_bytes.restype, L.bsa_select_workspace_bytes.argtypes = sz, [P]
         L.bsa_select_kv.restype = C.c_int
         L.bsa_select_kv.argtypes = [P, vp, vp, f64, f64, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+        L.bsa_select_kv_stat.restype = C.c_int
+        L.bsa_select_kv_stat.argtypes = [P, vp, vp, f64, f64, f64, vp, vp, i64, vp, vp, vp, vp, sz, vp]
         L.bsa_prune_q.restype, L.bsa_prune_q.argtypes = C.c_int, [P, vp, f64, vp, vp]
         L.bsa_attn_fwd.restype = C.c_int
         L.bsa_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp]
@@ -169,17 +171,29 @@ def alloc_kv_lists(shape: Shape, device, transpose: bool = True) -> KvLists:
 
 def select_kv(shape: Shape, Qbar: torch.Tensor, Kbar: torch.Tensor, threshold: float,
               score_scale: Optional[float] = None, out: Optional[KvLists] = None,
-              transpose: bool = True) -> KvLists:
+              transpose: bool = True, stat_z: Optional[float] = None) -> KvLists:
+    """stat_z: the standard-normal quantile of Eq. 3 (see stat_quantile); None = plain Eq. 4."""
     if out is None:
         out = alloc_kv_lists(shape, Qbar.device, transpose)
     if score_scale is None:
         score_scale = 1.0 / sqrt(shape.d)
-    st = lib().bsa_select_kv(C.byref(shape.c()), _ptr(Qbar), _ptr(Kbar), threshold, score_scale,
-                             _ptr(out.q2k_ptr), _ptr(out.q2k_idx), out.q2k_idx.numel(),
-                             _ptr(out.k2q_ptr), _ptr(out.k2q_idx), _ptr(out.nnz),
-                             _ptr(out.workspace), out.workspace.numel(), _stream())
+    tail = (_ptr(out.q2k_ptr), _ptr(out.q2k_idx), out.q2k_idx.numel(), _ptr(out.k2q_ptr), _ptr(out.k2q_idx),
+            _ptr(out.nnz), _ptr(out.workspace), out.workspace.numel(), _stream())
+    if stat_z is None:
+        st = lib().bsa_select_kv(C.byref(shape.c()), _ptr(Qbar), _ptr(Kbar), threshold, score_scale, *tail)
+    else:
+        st = lib().bsa_select_kv_stat(C.byref(shape.c()), _ptr(Qbar), _ptr(Kbar), threshold, stat_z, score_scale, *tail)
     _check(st, "bsa_select_kv")
     return out
+
+
+def stat_quantile(k: int, n: int) -> float:
+    """U(1 - k/n) of Eq. 3: the standard-normal quantile for k desired blocks of n."""
+    from statistics import NormalDist
+
+    if not 1 <= k <= n:
+        raise ValueError("1 <= k <= n")
+    return float("-inf") if k == n else NormalDist().inv_cdf(1.0 - k / n)
 
 
 def prune_q(shape: Shape, Q: torch.Tensor, keep_ratio: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -94,10 +94,10 @@ size_t bsa_select_workspace_bytes(const bsa_shape_t* shape) {
   return select_workspace_bytes(g);
 }
 
-int bsa_select_kv(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
-                  double threshold, double score_scale, int32_t* q2k_ptr, int32_t* q2k_idx,
-                  int64_t idx_capacity, int32_t* k2q_ptr, int32_t* k2q_idx, int64_t* nnz_dev,
-                  void* workspace, size_t workspace_bytes, void* stream) {
+static int select_common(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
+                         double threshold, double stat_z, double score_scale, int32_t* q2k_ptr,
+                         int32_t* q2k_idx, int64_t idx_capacity, int32_t* k2q_ptr, int32_t* k2q_idx,
+                         int64_t* nnz_dev, void* workspace, size_t workspace_bytes, void* stream) {
   Geom g;
   int rc = make_geom(shape, &g);
   if (rc) return rc;
@@ -107,8 +107,25 @@ int bsa_select_kv(const bsa_shape_t* shape, const double* Qbar, const double* Kb
   if (!std::isfinite(score_scale)) return BSA_ERR_RANGE;
   if (idx_capacity < (int64_t)g.rows * g.N) return BSA_ERR_CAPACITY;
   if (!workspace || workspace_bytes < select_workspace_bytes(g)) return BSA_ERR_WORKSPACE;
-  return launch_select(g, Qbar, Kbar, threshold, score_scale, q2k_ptr, q2k_idx, k2q_ptr, k2q_idx,
+  return launch_select(g, Qbar, Kbar, threshold, stat_z, score_scale, q2k_ptr, q2k_idx, k2q_ptr, k2q_idx,
                        nnz_dev, workspace, (hipStream_t)stream);
+}
+
+int bsa_select_kv(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
+                  double threshold, double score_scale, int32_t* q2k_ptr, int32_t* q2k_idx,
+                  int64_t idx_capacity, int32_t* k2q_ptr, int32_t* k2q_idx, int64_t* nnz_dev,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+  return select_common(shape, Qbar, Kbar, threshold, (double)NAN, score_scale, q2k_ptr, q2k_idx,
+                       idx_capacity, k2q_ptr, k2q_idx, nnz_dev, workspace, workspace_bytes, stream);
+}
+
+int bsa_select_kv_stat(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
+                       double threshold, double stat_z, double score_scale, int32_t* q2k_ptr,
+                       int32_t* q2k_idx, int64_t idx_capacity, int32_t* k2q_ptr, int32_t* k2q_idx,
+                       int64_t* nnz_dev, void* workspace, size_t workspace_bytes, void* stream) {
+  if (stat_z != stat_z) return BSA_ERR_RANGE;  // NaN
+  return select_common(shape, Qbar, Kbar, threshold, stat_z, score_scale, q2k_ptr, q2k_idx,
+                       idx_capacity, k2q_ptr, k2q_idx, nnz_dev, workspace, workspace_bytes, stream);
 }
 
 int bsa_prune_q(const bsa_shape_t* shape, const void* Q, double keep_ratio, int32_t* keep_idx,

@@ -114,15 +114,15 @@ __device__ inline double wave_sum(double v) {
 }
 
 template <int NW, int MAXE>
-__global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const double* S, double p,
+__global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const double* S, double p, double zq,
                                                             uint32_t* mask, int32_t* cnt) {
   constexpr int NT = 64 * NW;
   extern __shared__ __align__(16) uint8_t smem[];
   unsigned long long* lkey = reinterpret_cast<unsigned long long*>(smem);  // [N], for the equal-score path
   __shared__ double red[NW];
   __shared__ int redc[NW];
+  __shared__ unsigned long long rk[2][NW];
   __shared__ uint32_t bits[256];
-  __shared__ unsigned long long pick;
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const double* s = S + (int64_t)row * g.N;
   const int ept = (g.N + NT - 1) / NT;  // elements per thread actually used (<= MAXE): j = e*NT + tid
@@ -138,6 +138,17 @@ __global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const doubl
 #pragma unroll
     for (int w = 1; w < NW; ++w) t = __dadd_rn(t, red[w]);
     return t;
+  };
+  auto block_max = [&](double v) -> double {
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) v = fmax(v, __shfl_xor(v, m));
+    if (NW == 1) return v;
+    __syncthreads();
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) v = fmax(v, red[w]);
+    return v;
   };
   auto block_count = [&](int c) -> int {  // c is wave-uniform
     if (NW == 1) return c;
@@ -158,14 +169,7 @@ __global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const doubl
     sv[e] = (e < ept && j < g.N) ? s[j] : -INFINITY;
     smax = fmax(smax, sv[e]);
   }
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) smax = fmax(smax, __shfl_xor(smax, m));
-  if (NW > 1) {
-    if (lane == 0) red[wave] = smax;
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < NW; ++w) smax = fmax(smax, red[w]);
-  }
+  smax = block_max(smax);
   for (int k = tid; k < 256; k += NT) bits[k] = 0u;
 
   unsigned long long key[MAXE];
@@ -186,33 +190,43 @@ __global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const doubl
     }
   }
   const double Z = block_sum(zl);
-  int kstar = g.N;
-  bool all = true;
+  // smallest and largest key of the row
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) {
+    const unsigned long long a = __shfl_xor(kmin, m), b = __shfl_xor(kmax, m);
+    kmin = a < kmin ? a : kmin;
+    kmax = b > kmax ? b : kmax;
+  }
+  if (NW > 1) {
+    __syncthreads();
+    if (lane == 0) { rk[0][wave] = kmin; rk[1][wave] = kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      kmin = rk[0][w] < kmin ? rk[0][w] : kmin;
+      kmax = rk[1][w] > kmax ? rk[1][w] : kmax;
+    }
+  }
+  auto count_where = [&](unsigned long long lo_incl, bool equal_only) -> int {  // keys >= lo (or == lo)
+    int cl = 0;
+#pragma unroll
+    for (int e = 0; e < MAXE; ++e)
+      if (e < ept) cl += __popcll(__ballot(equal_only ? key[e] == lo_incl : key[e] >= lo_incl));
+    return block_count(cl);
+  };
+
+  // The selection is "every key above `last`, plus the first `need` blocks (ascending id)
+  // whose key equals `last`"; `tie` says that several blocks share that key.
+  int kstar = g.N, need = 1;
+  bool all = true, tie = false;
+  unsigned long long last = 0ull;
   if (p < 1.0) {
     all = false;
     const double target = __dmul_rn(p, Z);
-    // common prefix of all keys: the bracket starts there
-#pragma unroll
-    for (int m = 32; m > 0; m >>= 1) {
-      const unsigned long long a = __shfl_xor(kmin, m), b = __shfl_xor(kmax, m);
-      kmin = a < kmin ? a : kmin;
-      kmax = b > kmax ? b : kmax;
-    }
-    if (NW > 1) {
-      __shared__ unsigned long long rk[2][NW];
-      __syncthreads();
-      if (lane == 0) { rk[0][wave] = kmin; rk[1][wave] = kmax; }
-      __syncthreads();
-#pragma unroll
-      for (int w = 0; w < NW; ++w) {
-        kmin = rk[0][w] < kmin ? rk[0][w] : kmin;
-        kmax = rk[1][w] > kmax ? rk[1][w] : kmax;
-      }
-    }
     const unsigned long long diff = kmin ^ kmax;
     int b = diff ? 63 - __builtin_clzll(diff) : -1;  // highest bit in which two keys differ
     unsigned long long lo = b >= 0 ? (kmin >> b >> 1 << 1 << b) : kmin;  // keys' common prefix, lower bits zero
-    int cnt_lo = g.N, cnt_hi = 0;  // keys >= lo; keys >= hi, hi = lo + 2^(b+1) (not representable when b = 63: never needed)
+    int cnt_lo = g.N, cnt_hi = 0;  // keys >= lo; keys >= hi, hi = lo + 2^(b+1)
     for (; b >= 0 && cnt_lo - cnt_hi > 1; --b) {
       const unsigned long long cand = lo | (1ull << b);
       double gl = 0.0;
@@ -234,10 +248,10 @@ __global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const doubl
         cnt_hi = c;
       }
     }
-    // the keys still inside the bracket are all equal (one key, unless scores tie exactly)
-    const unsigned long long hi_excl_span = b >= 0 ? (1ull << b << 1) : 1ull;  // bracket = [lo, lo + span), span 0 means up to 2^64
-    int need = 1;
-    if (cnt_lo - cnt_hi > 1) {  // equal scores: add them one at a time, as the sorted prefix would
+    // the keys still inside the bracket [lo, lo + span) are all equal (one key, unless scores tie exactly)
+    const unsigned long long span = b >= 0 ? (1ull << b << 1) : 1ull;  // 0 stands for 2^64
+    tie = cnt_lo - cnt_hi > 1;
+    if (tie) {  // equal scores: add them one at a time, as the sorted prefix would
       double gl = 0.0, el = 0.0;
 #pragma unroll
       for (int e = 0; e < MAXE; ++e) {
@@ -247,16 +261,7 @@ __global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const doubl
         }
       }
       double c = block_sum(gl);
-      // the mass of one tied element (identical in all of them): take the maximum over threads
-#pragma unroll
-      for (int m = 32; m > 0; m >>= 1) el = fmax(el, __shfl_xor(el, m));
-      if (NW > 1) {
-        __syncthreads();
-        if (lane == 0) red[wave] = el;
-        __syncthreads();
-#pragma unroll
-        for (int w = 0; w < NW; ++w) el = fmax(el, red[w]);
-      }
+      el = block_max(el);  // the mass of one tied element (identical in all of them)
       const int tied = cnt_lo - cnt_hi;
       need = 0;
       do {
@@ -265,18 +270,64 @@ __global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const doubl
       } while (c < target && need < tied);
     }
     kstar = cnt_hi + need;
-    // the last selected key: the unique key of the bracket
-    unsigned long long last = 0ull;
+    // the last selected key: the one key value inside the bracket
+    unsigned long long lk = 0ull;
 #pragma unroll
     for (int e = 0; e < MAXE; ++e)
-      if (e < ept && key[e] >= lo && (hi_excl_span == 0ull || key[e] - lo < hi_excl_span) && key[e] > last) last = key[e];
-    if (tid == 0) pick = 0ull;
-    __syncthreads();
-    if (last) atomicMax(&pick, last);
-    __syncthreads();
-    last = pick;
-    // mark every key above `last`, and the first `need` blocks whose key equals it
-    const bool tie = cnt_lo - cnt_hi > 1;
+      if (e < ept && key[e] >= lo && (span == 0ull || key[e] - lo < span) && key[e] > lk) lk = key[e];
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) {
+      const unsigned long long o = __shfl_xor(lk, m);
+      lk = o > lk ? o : lk;
+    }
+    if (NW > 1) {
+      __syncthreads();
+      if (lane == 0) rk[0][wave] = lk;
+      __syncthreads();
+#pragma unroll
+      for (int w = 0; w < NW; ++w) lk = rk[0][w] > lk ? rk[0][w] : lk;
+    }
+    last = lk;
+  }
+
+  // Eq. 3 (statistical dynamic threshold): only blocks whose score reaches
+  // tau = mean + std * zq are candidates; they are a prefix of the same order, so the filter
+  // can only shorten the selection.  No candidate: the best block alone.
+  if (zq == zq && zq != -INFINITY) {
+    double sl = 0.0;
+#pragma unroll
+    for (int e = 0; e < MAXE; ++e)
+      if (e < ept && e * NT + tid < g.N) sl = __dadd_rn(sl, sv[e]);
+    const double mean = __ddiv_rn(block_sum(sl), (double)g.N);
+    double dl = 0.0;
+#pragma unroll
+    for (int e = 0; e < MAXE; ++e)
+      if (e < ept && e * NT + tid < g.N) {
+        const double dvn = __dadd_rn(sv[e], -mean);
+        dl = __dadd_rn(dl, __dmul_rn(dvn, dvn));
+      }
+    const double var = g.N > 1 ? __ddiv_rn(block_sum(dl), (double)(g.N - 1)) : 0.0;
+    const double tau = __dadd_rn(mean, __dmul_rn(__dsqrt_rn(var), zq));
+    const unsigned long long ktau = order_key(tau);
+    const int ncand = tau == tau ? count_where(ktau, false) : 0;
+    if (ncand < kstar) {
+      all = false;
+      if (ncand >= 1) {
+        kstar = ncand;
+        last = ktau;  // "above last, or equal to it": every key >= ktau
+        tie = false;
+        need = 1;
+      } else {
+        kstar = 1;
+        last = kmax;
+        need = 1;
+        tie = count_where(kmax, true) > 1;
+      }
+    }
+  }
+
+  if (!all) {
+    if (NW > 1) __syncthreads();  // bits[] cleared by everyone
 #pragma unroll
     for (int e = 0; e < MAXE; ++e) {
       const int j = e * NT + tid;
@@ -386,7 +437,7 @@ __global__ __launch_bounds__(256) void transpose_kernel(Geom g, const uint32_t* 
   if (!FILL && lane < 32 && col < g.N) kcnt[(int64_t)bh * g.N + col] = acc;
 }
 
-int launch_select(const Geom& g, const double* Qbar, const double* Kbar, double threshold,
+int launch_select(const Geom& g, const double* Qbar, const double* Kbar, double threshold, double stat_z,
                   double score_scale, int32_t* q2k_ptr, int32_t* q2k_idx, int32_t* k2q_ptr,
                   int32_t* k2q_idx, int64_t* nnz_dev, void* ws, hipStream_t st) {
   SelectWs w = carve(g, ws);
@@ -395,14 +446,14 @@ int launch_select(const Geom& g, const double* Qbar, const double* Kbar, double 
                      g, Qbar, Kbar, score_scale, w.scores);
   const size_t lds = (size_t)g.N * sizeof(unsigned long long);  // <= 64 KB
   if (g.N <= 1024)
-    hipLaunchKernelGGL((row_select_kernel<1, 16>), dim3(g.rows), dim3(64), lds, st, g, w.scores, threshold, w.mask, w.cnt);
+    hipLaunchKernelGGL((row_select_kernel<1, 16>), dim3(g.rows), dim3(64), lds, st, g, w.scores, threshold, stat_z, w.mask, w.cnt);
   else if (g.N <= 4096)
-    hipLaunchKernelGGL((row_select_kernel<4, 16>), dim3(g.rows), dim3(256), lds, st, g, w.scores, threshold, w.mask, w.cnt);
+    hipLaunchKernelGGL((row_select_kernel<4, 16>), dim3(g.rows), dim3(256), lds, st, g, w.scores, threshold, stat_z, w.mask, w.cnt);
   else {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(row_select_kernel<4, 32>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return BSA_ERR_LAUNCH;
-    hipLaunchKernelGGL((row_select_kernel<4, 32>), dim3(g.rows), dim3(256), lds, st, g, w.scores, threshold, w.mask, w.cnt);
+    hipLaunchKernelGGL((row_select_kernel<4, 32>), dim3(g.rows), dim3(256), lds, st, g, w.scores, threshold, stat_z, w.mask, w.cnt);
   }
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, w.cnt, g.rows, q2k_ptr, nnz_dev);
   hipLaunchKernelGGL(expand_kernel, dim3((g.rows + 3) / 4), dim3(256), 0, st, g, w.mask, q2k_ptr, q2k_idx);

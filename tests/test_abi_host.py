@@ -72,6 +72,8 @@ def test_null_range_capacity_workspace_errors_come_before_any_launch():
     assert sel(cap=rows_n - 1) == -4
     assert sel(ws=None) == -7 and sel(wsb=ws - 1) == -7
     assert sel(kp=None) == -1  # k2q pointers: both or neither
+    stat = lambda z, **k: lib.bsa_select_kv_stat(s, k.get("qb", p), p, 0.9, z, 0.125, p, p, k.get("cap", rows_n), p, p, None, p, ws, None)
+    assert stat(float("nan")) == -3 and stat(0.5, qb=None) == -1 and stat(float("-inf"), cap=rows_n - 1) == -4
     assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 0, 0.125, p, p, None, 0, None) == -3
     assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 33, 0.125, p, p, None, 0, None) == -3
     assert lib.bsa_attn_fwd(s, p, p, None, p, p, p, 16, 0.125, p, p, None, 0, None) == -1

@@ -104,3 +104,53 @@ def test_signed_zero_and_negative_scores():
     Kbar[0, 30:34] *= -0.0
     host = run(shp, Qbar, Kbar, 0.95)
     check(shp, host, Qbar, Kbar, 0.95)
+
+
+@pytest.mark.parametrize("N,k,p", [(520, 52, 0.9), (520, 260, 0.5), (520, 5, 1.0), (1032, 100, 0.95), (40, 40, 0.8), (64, 1, 0.9)])
+def test_statistical_threshold_filter(N, k, p):
+    """Eq. 3 ahead of Eq. 4: candidates are the blocks whose logit reaches mean + std * z."""
+    U.progress(f"select stat N={N} k={k} p={p}")
+    H, d = 2, 32
+    rng = np.random.default_rng(7 * N + k)
+    shp = select_shape(N, H, d)
+    Qbar = rng.standard_normal((H, N, d)) * 1.5
+    Kbar = rng.standard_normal((H, N, d)) * 1.5
+    z = B.stat_quantile(k, N)
+    assert z == o.stat_quantile(k, N)
+    q = torch.from_numpy(Qbar).cuda().reshape(1, H, N, d)
+    kk = torch.from_numpy(Kbar).cuda().reshape(1, H, N, d)
+    host = U.lists_to_host(shp, B.select_kv(shp, q, kk, p, stat_z=z))
+    scale = 1.0 / sqrt(d)
+    shorter = 0
+    for h in range(H):
+        scores = o.block_scores(Qbar[h], Kbar[h], scale)
+        ptr, idx, margin = o.select_kv(scores, p, z)
+        plain, _, _ = o.select_kv(scores, p)
+        shorter += int(ptr[-1] < plain[-1])
+        gptr, gidx = U.head_csr(host, shp, 0, h, "q2k")
+        if not (np.array_equal(gptr, ptr) and np.array_equal(gidx, idx)):
+            for i in range(N):  # a differing row must sit within rounding of a deciding comparison
+                if not np.array_equal(gidx[gptr[i]:gptr[i + 1]], idx[ptr[i]:ptr[i + 1]]):
+                    assert o.select_row(scores[i], p, z).margin < U.SELECT_MARGIN, (h, i)
+            continue
+        tptr, tidx = o.transpose_csr(ptr, idx, N)
+        kptr, kidx = U.head_csr(host, shp, 0, h, "k2q")
+        assert np.array_equal(kptr, tptr) and np.array_equal(kidx, tidx)
+    if k < N // 2 and p >= 0.9:
+        assert shorter == H  # the filter is active in these cases, not vacuous
+
+
+def test_statistical_threshold_with_no_candidate_keeps_the_best_block():
+    U.progress("select stat no candidate")
+    N, H, d = 64, 1, 8
+    shp = select_shape(N, H, d)
+    rng = np.random.default_rng(3)
+    Qbar, Kbar = rng.standard_normal((H, N, d)), rng.standard_normal((H, N, d))
+    Kbar[0, 5] = Kbar[0, 9]  # an exact tie that may be a row's maximum: lowest id wins
+    q = torch.from_numpy(Qbar).cuda().reshape(1, H, N, d)
+    k = torch.from_numpy(Kbar).cuda().reshape(1, H, N, d)
+    host = U.lists_to_host(shp, B.select_kv(shp, q, k, 0.9, stat_z=float("inf")))
+    ptr, idx = U.head_csr(host, shp, 0, 0, "q2k")
+    scores = o.block_scores(Qbar[0], Kbar[0], 1.0 / sqrt(d))
+    assert np.array_equal(np.diff(ptr), np.ones(N, dtype=np.int32))
+    assert np.array_equal(idx, scores.argmax(axis=1))  # argmax returns the first maximum
