@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--sigma", type=float, default=None)
     ap.add_argument("--threshold", type=float, default=None)
     ap.add_argument("--keep-ratio", type=float, default=None)
+    ap.add_argument("--block-major", action="store_true",
+                    help="hold the tensors in block-major token order (the tokens of a block adjacent) instead of raster order")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-heads", type=int, default=3, help="heads of the workload the CPU oracle is timed on")
@@ -95,7 +97,7 @@ def cpu_baseline(wl, heads: int):
     from bsa_workloads import head_inputs
     from oracle import bsa_oracle as o
 
-    part = o.Partition(*wl.grid, *wl.block, *wl.window)
+    part = o.Partition(*wl.grid, *wl.block, *wl.window, wl.block_major)
     dtype = np.float64 if wl.L <= 4096 else np.float32  # attention GEMMs; decisions are always fp64
     t = 0.0
     for h in range(heads):
@@ -122,7 +124,7 @@ def sweep(args, torch, B):
         for p in (0.5, 0.8, 0.9, 0.95):
             for r in (0.25, 0.5, 1.0):
                 wl = base.replace(sigma=sigma, threshold=p, keep_ratio=r, seed=point)
-                shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16, *wl.window)
+                shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16, *wl.window, int(wl.block_major))
                 x = make_inputs(wl, torch)
                 Q, K, V, dO = x["Q"], x["K"], x["V"], x["dO"]
                 nk = B.n_keep(shp, r)
@@ -228,9 +230,11 @@ def main():
         return
     wl = WORKLOADS[args.workload]
     over = {k: v for k, v in (("sigma", args.sigma), ("threshold", args.threshold), ("keep_ratio", args.keep_ratio)) if v is not None}
+    if args.block_major:
+        over["block_major"] = True
     if over:
         wl = wl.replace(**over)
-    shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16, *wl.window)
+    shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16, *wl.window, int(wl.block_major))
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     x = make_inputs(wl, torch)
@@ -307,7 +311,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "H": wl.H, "d": wl.d, "grid": list(wl.grid), "block": list(wl.block),
-                   "tokens": wl.L, "threshold": wl.threshold, "keep_ratio": wl.keep_ratio, "sigma": wl.sigma},
+                   "tokens": wl.L, "threshold": wl.threshold, "keep_ratio": wl.keep_ratio, "sigma": wl.sigma,
+                   "window": list(wl.window), "layout": "block_major" if wl.block_major else "raster"},
         "selected_block_fraction": f, "nnz": nnz, "n_keep": nk,
         "ms_per_call": parts,
         "effective_tflops": dense_flops / (ms_step * 1e-3) / 1e12,

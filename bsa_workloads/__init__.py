@@ -11,6 +11,7 @@ from .video_fields import (  # noqa: F401
     TENSOR_NAMES,
     head_tensor,
     head_inputs,
+    block_major_order,
     bf16_round,
     bf16_bits,
     bf16_from_bits,

@@ -37,6 +37,7 @@ class Workload:
     keep_ratio: float = 0.5
     seed: int = 0
     window: Tuple[int, int, int] = (0, 0, 0)  # critical-token window; zeros = the whole block
+    block_major: bool = False  # token order of the tensors: raster, or the tokens of a block adjacent
 
     @property
     def L(self) -> int:
@@ -113,7 +114,7 @@ def _smooth_field(rng: np.random.Generator, grid, d: int) -> np.ndarray:
 
 
 def head_tensor(wl: Workload, which: str, b: int, h: int) -> np.ndarray:
-    """One [L, d] float32 slice of tensor `which` in raster token order.
+    """One [L, d] float32 slice of tensor `which` in the workload's token order.
 
     For bf16 workloads the values are already rounded to bfloat16, so what
     the CPU oracle reads equals what the device holds."""
@@ -127,7 +128,18 @@ def head_tensor(wl: Workload, which: str, b: int, h: int) -> np.ndarray:
         x = (field + np.float64(wl.sigma) * noise).astype(np.float32)
     if wl.dtype == "bf16":
         x = bf16_round(x)
+    if wl.block_major:  # the same video, rows reordered so that the tokens of a block are adjacent
+        x = np.ascontiguousarray(x[block_major_order(wl.grid, wl.block)])
     return x
+
+
+def block_major_order(grid: Tuple[int, int, int], block: Tuple[int, int, int]) -> np.ndarray:
+    """order[i*Bk + c] = raster index of intra-block token c of block i (blocks and the tokens
+    inside a block both numbered raster-wise): a pure index permutation, no arithmetic."""
+    T, Hs, Ws = grid
+    Ct, Ch, Cw = block
+    n = np.arange(T * Hs * Ws, dtype=np.int64).reshape(T // Ct, Ct, Hs // Ch, Ch, Ws // Cw, Cw)
+    return n.transpose(0, 2, 4, 1, 3, 5).reshape(-1)
 
 
 def head_inputs(wl: Workload, b: int, h: int) -> Dict[str, np.ndarray]:

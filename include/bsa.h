@@ -11,8 +11,9 @@
  * Conventions shared by every entry point
  *   - All data pointers are DEVICE pointers on the current HIP device unless stated,
  *     16-byte aligned (tensors, workspaces) or 4-byte aligned (index arrays).
- *   - Q, K, V, O, dO, dQ, dK, dV are contiguous [B, H, L, d] in RASTER token order
- *     n = t*Hs*Ws + h*Ws + w (Sec. 3.1), L = T*Hs*Ws; element type per shape.dtype.
+ *   - Q, K, V, O, dO, dQ, dK, dV are contiguous [B, H, L, d], L = T*Hs*Ws, in RASTER token
+ *     order n = t*Hs*Ws + h*Ws + w (Sec. 3.1) unless shape.layout says block-major;
+ *     element type per shape.dtype.
  *   - Blocks: (Ct, Ch, Cw) must divide (T, Hs, Ws) (Sec. 3.2.1).  Bk = Ct*Ch*Cw tokens
  *     per block, N = L / Bk blocks, block id = (bt*Nh + bh)*Nw + bw, intra-block id
  *     = (ct*Ch + ch)*Cw + cw.  "rows" = B*H*N (one row per head and query block).
@@ -36,6 +37,12 @@ extern "C" {
 
 enum bsa_dtype { BSA_F32 = 0, BSA_BF16 = 1 };
 
+/* Token order of the [B,H,L,d] tensors.  RASTER: n = t*Hs*Ws + h*Ws + w (Sec. 3.1).
+ * BLOCK_MAJOR: the one-time reorder of Sec. 3.2.1, tokens of a block adjacent: row
+ * i*Bk + c holds intra-block token c of block i.  Both layouts give the same results for
+ * the same video, token for token. */
+enum bsa_layout { BSA_LAYOUT_RASTER = 0, BSA_LAYOUT_BLOCK_MAJOR = 1 };
+
 enum bsa_status {
   BSA_OK = 0,
   BSA_ERR_NULL = -1,        /* a required pointer is NULL */
@@ -57,6 +64,7 @@ typedef struct bsa_shape {
                             must divide (Ct, Ch, Cw) evenly; 0,0,0 = the whole block, one critical
                             token per block.  Windows are numbered raster-wise over the block's
                             window grid; a window's critical token is its local (Wt/2, Wh/2, Ww/2). */
+  int32_t layout;        /* enum bsa_layout of every [B,H,L,d] tensor */
 } bsa_shape_t;
 
 /* Limits: Bk <= 256, N <= 8192, d % 8 == 0 and d <= 256. */

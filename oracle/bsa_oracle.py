@@ -69,6 +69,9 @@ class Partition:
     Wt: int = 0
     Wh: int = 0
     Ww: int = 0
+    # Token order of the tensors: raster (Sec. 3.1), or after the one-time reorder of
+    # Sec. 3.2.1 that makes the tokens of a block adjacent (row i*Bk + c = token c of block i).
+    block_major: bool = False
 
     def __post_init__(self):
         if min(self.T, self.Hs, self.Ws, self.Ct, self.Ch, self.Cw) <= 0:
@@ -156,11 +159,13 @@ class Partition:
         return self.nwin * self.n_keep_window(r)
 
     def block_tokens(self) -> np.ndarray:
-        """tok[i, c] = raster index of intra-block token c of block i.
+        """tok[i, c] = row (raster index, or i*Bk + c in block-major order) of intra-block token c of block i.
 
         Blocks are numbered raster-wise over the block grid, tokens raster-wise
         inside the block."""
         nt, nh, nw = self.nblk
+        if self.block_major:
+            return np.arange(self.N * self.Bk, dtype=np.int64).reshape(self.N, self.Bk)
         tok = np.empty((self.N, self.Bk), dtype=np.int64)
         for bt in range(nt):
             for bh in range(nh):

@@ -19,6 +19,7 @@ import torch
 _LIB_PATH = os.environ.get("BSA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libbsa.so")
 
 F32, BF16 = 0, 1
+RASTER, BLOCK_MAJOR = 0, 1
 EXPORTS = (
     "bsa_strerror", "bsa_n_keep", "bsa_pool_blocks", "bsa_select_workspace_bytes", "bsa_select_kv",
     "bsa_select_kv_stat", "bsa_prune_q", "bsa_fwd_workspace_bytes", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd", "bsa_attn_bwd_stages",
@@ -33,7 +34,7 @@ class BsaError(RuntimeError):
 
 
 class ShapeStruct(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("B", "H", "T", "Hs", "Ws", "Ct", "Ch", "Cw", "d", "dtype", "Wt", "Wh", "Ww")]
+    _fields_ = [(n, C.c_int32) for n in ("B", "H", "T", "Hs", "Ws", "Ct", "Ch", "Cw", "d", "dtype", "Wt", "Wh", "Ww", "layout")]
 
 
 _lib = None
@@ -89,6 +90,7 @@ class Shape:
     Wt: int = 0  # window of the critical-token mechanism; 0, 0, 0 = the whole block
     Wh: int = 0
     Ww: int = 0
+    layout: int = 0  # RASTER or BLOCK_MAJOR
 
     @property
     def L(self) -> int:
@@ -112,7 +114,7 @@ class Shape:
 
     def c(self) -> ShapeStruct:
         return ShapeStruct(self.B, self.H, self.T, self.Hs, self.Ws, self.Ct, self.Ch, self.Cw, self.d, self.dtype,
-                           self.Wt, self.Wh, self.Ww)
+                           self.Wt, self.Wh, self.Ww, self.layout)
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:

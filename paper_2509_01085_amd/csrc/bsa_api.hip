@@ -33,6 +33,8 @@ int make_geom(const bsa_shape_t* s, Geom* g) {
   if (s->Ct % g->Wt || s->Ch % g->Wh || s->Cw % g->Ww) return BSA_ERR_SHAPE;
   g->Wk = g->Wt * g->Wh * g->Ww;
   g->nwin = g->Bk / g->Wk;
+  if (s->layout != BSA_LAYOUT_RASTER && s->layout != BSA_LAYOUT_BLOCK_MAJOR) return BSA_ERR_SHAPE;
+  g->tiled = s->layout == BSA_LAYOUT_BLOCK_MAJOR;
   g->dense = 0;
   g->inv_Nw = g->Nw == 1 ? 0u : (uint32_t)(0x100000000ull / (uint32_t)g->Nw) + 1u;
   g->inv_NwNh = g->Nw * g->Nh == 1 ? 0u : (uint32_t)(0x100000000ull / (uint32_t)(g->Nw * g->Nh)) + 1u;
@@ -213,6 +215,7 @@ static int dense_geom(const bsa_shape_t* shape, Geom* g) {
   int rc = make_geom(shape, g);
   if (rc) return rc;
   g->dense = 1;
+  g->tiled = 1;
   return BSA_OK;
 }
 

@@ -18,13 +18,14 @@ struct Geom {
   int rows;        // B*H*N
   int Wt, Wh, Ww;  // window of the critical-token mechanism (Sec. 3.2.2); the whole block when one center per block
   int nwin, Wk;    // windows per block, tokens per window
-  int dense;       // 1: tiles are runs of Bk consecutive raster tokens (dense baseline)
+  int tiled;       // 1: the Bk tokens of block i are the consecutive rows i*Bk .. i*Bk+Bk-1 (block-major layout)
+  int dense;       // 1: dense baseline: every pair listed, nothing pruned (implies tiled)
   uint32_t inv_Nw, inv_NwNh;  // floor(2^32 / x) + 1 (0 when x == 1): n / x == umulhi(n, inv) for n < 2^16
 };
 
 // Raster index (Sec. 3.1) of intra-block token c of block i (Sec. 3.2.1).
 __host__ __device__ inline int token_of(const Geom& g, int i, int c) {
-  if (g.dense) return i * g.Bk + c;
+  if (g.tiled) return i * g.Bk + c;
   const int bw = i % g.Nw, bh = (i / g.Nw) % g.Nh, bt = i / (g.Nw * g.Nh);
   const int cw = c % g.Cw, ch = (c / g.Cw) % g.Ch, ct = c / (g.Cw * g.Ch);
   return ((bt * g.Ct + ct) * g.Hs + (bh * g.Ch + ch)) * g.Ws + (bw * g.Cw + cw);
@@ -32,14 +33,14 @@ __host__ __device__ inline int token_of(const Geom& g, int i, int c) {
 
 // Raster index of the first token (intra-block id 0) of block i.
 __host__ __device__ inline int block_origin(const Geom& g, int i) {
-  if (g.dense) return i * g.Bk;
+  if (g.tiled) return i * g.Bk;
   const int bw = i % g.Nw, bh = (i / g.Nw) % g.Nh, bt = i / (g.Nw * g.Nh);
   return ((bt * g.Ct) * g.Hs + bh * g.Ch) * g.Ws + bw * g.Cw;
 }
 
 // Same, division-free (block ids are < 2^16): for per-tile use inside pipelined loops.
 __device__ inline int block_origin_fast(const Geom& g, int i) {
-  if (g.dense) return i * g.Bk;
+  if (g.tiled) return i * g.Bk;
   const int bt = g.inv_NwNh ? (int)__umulhi((uint32_t)i, g.inv_NwNh) : i;
   const int rem = i - bt * g.Nw * g.Nh;
   const int bh = g.inv_Nw ? (int)__umulhi((uint32_t)rem, g.inv_Nw) : rem;
@@ -49,7 +50,7 @@ __device__ inline int block_origin_fast(const Geom& g, int i) {
 
 // Offset of intra-block token c from the block origin, in tokens.
 __host__ __device__ inline int intra_offset(const Geom& g, int c) {
-  if (g.dense) return c;
+  if (g.tiled) return c;
   const int cw = c % g.Cw, ch = (c / g.Cw) % g.Ch, ct = c / (g.Cw * g.Ch);
   return (ct * g.Hs + ch) * g.Ws + cw;
 }

@@ -35,11 +35,11 @@ def progress(msg: str) -> None:
 
 
 def shape_of(wl: Workload) -> B.Shape:
-    return B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16, *wl.window)
+    return B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.F32 if wl.dtype == "fp32" else B.BF16, *wl.window, int(wl.block_major))
 
 
 def part_of(wl: Workload) -> o.Partition:
-    return o.Partition(*wl.grid, *wl.block, *wl.window)
+    return o.Partition(*wl.grid, *wl.block, *wl.window, wl.block_major)
 
 
 def device_inputs(wl: Workload, names=("Q", "K", "V", "dO"), heads: Optional[Iterable[int]] = None) -> Dict[str, torch.Tensor]:

@@ -49,6 +49,11 @@ CASES = {
     "win_wan_r75": Workload("win_wan_r75", 1, 2, 64, "bf16", (8, 8, 12), (4, 4, 4), threshold=0.7, keep_ratio=0.75, window=(2, 4, 4)),
     "win_split": Workload("win_split", 1, 2, 128, "bf16", (16, 16, 24), (4, 4, 4), threshold=0.7, window=(2, 2, 2), seed=3),
     "win_ragged": Workload("win_ragged", 1, 2, 72, "fp32", (6, 6, 8), (3, 2, 4), threshold=0.7, keep_ratio=0.5, window=(1, 2, 4)),
+    # block-major token order (the one-time reorder of Sec. 3.2.1) of the same videos
+    "bm_tiny": WORKLOADS["tiny"].replace(block_major=True, threshold=0.6, seed=1),
+    "bm_wan": Workload("mini_wan", 1, 2, 128, "bf16", (8, 8, 12), (4, 4, 4), threshold=0.6, block_major=True),
+    "bm_win_split": Workload("win_split", 1, 2, 128, "bf16", (16, 16, 24), (4, 4, 4), threshold=0.7, window=(2, 2, 2), seed=3,
+                             block_major=True),
     # threshold 1: every block selected
     "p_one": Workload("p_one", 1, 1, 64, "bf16", (4, 8, 8), (2, 4, 4), threshold=1.0, keep_ratio=0.5),
 }
@@ -191,3 +196,21 @@ def test_sparse_path_at_threshold_one_equals_dense_path():
     torch.cuda.synchronize()
     assert U.rel_err(U.host_f64(O), U.host_f64(Od)) < 2e-2
     assert (LSE - Ld).abs().max().item() < 2e-2
+
+
+@pytest.mark.parametrize("raster,tiled", [("tiny_p60", "bm_tiny"), ("mini_wan", "bm_wan"), ("win_split", "bm_win_split")])
+def test_block_major_layout_is_a_pure_permutation_of_the_raster_results(raster, tiled):
+    """Same video, two token orders: every output of the block-major run is the raster run's
+    output with its rows reordered, bit for bit (same tiles, same arithmetic order)."""
+    from bsa_workloads import block_major_order
+
+    a, b = run_case(raster), run_case(tiled)
+    wl = a["wl"]
+    assert b["wl"].replace(block_major=False) == wl.replace(name=b["wl"].name)
+    order = torch.from_numpy(block_major_order(wl.grid, wl.block)).cuda()
+    assert torch.equal(a["lists"].q2k_ptr, b["lists"].q2k_ptr) and torch.equal(a["keep"], b["keep"])
+    nnz = a["host"]["nnz"]
+    assert torch.equal(a["lists"].q2k_idx[:nnz], b["lists"].q2k_idx[:nnz])
+    for name in ("O", "dQ", "dK", "dV"):
+        assert torch.equal(a[name][:, :, order], b[name]), name
+    assert torch.equal(a["LSE"][:, :, order], b["LSE"])

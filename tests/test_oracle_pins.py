@@ -521,3 +521,30 @@ def test_stat_threshold_hand_example_and_invariances():
             got = o.select_row(r, p, z).idx.tolist()
             want = sorted(set(full) & set(cand)) or [int(np.argmax(r))]
             assert got == want
+
+
+# ------------------------------------------------ block-major token order (Sec. 3.2.1 reorder)
+def test_block_major_order_is_the_partitions_block_table():
+    from bsa_workloads import block_major_order
+
+    part = o.Partition(4, 6, 8, 2, 3, 4)
+    assert np.array_equal(block_major_order((4, 6, 8), (2, 3, 4)), part.block_tokens().reshape(-1))
+    bm = o.Partition(4, 6, 8, 2, 3, 4, 0, 0, 0, True)
+    assert np.array_equal(bm.block_tokens().reshape(-1), np.arange(bm.L))
+    assert bm.center == part.center and np.array_equal(bm.window_of(), part.window_of())
+
+
+def test_block_major_layout_gives_the_same_video_the_same_results():
+    """Reordering the tokens once (blocks adjacent) and telling the partition so must permute
+    every output and change nothing else: the method is defined on the video, not on the order."""
+    part = win_part()
+    bm = o.Partition(*TINY.grid, *TINY.block, 1, 2, 2, True)
+    order = part.block_tokens().reshape(-1)
+    x = tiny_inputs(1)
+    x["Q"], x["K"] = x["Q"] * 3.0, x["K"] * 3.0
+    xb = {k: v[order] for k, v in x.items()}
+    a = o.bsa_head(x["Q"], x["K"], x["V"], x["dO"], part, 0.6, 0.5)
+    b = o.bsa_head(xb["Q"], xb["K"], xb["V"], xb["dO"], bm, 0.6, 0.5)
+    assert np.array_equal(a[0].q2k_idx, b[0].q2k_idx) and np.array_equal(a[0].keep_idx, b[0].keep_idx)
+    for ta, tb in zip(a[1:], b[1:]):
+        assert np.array_equal(ta[order], tb)
