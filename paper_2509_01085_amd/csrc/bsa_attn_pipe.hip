@@ -986,19 +986,37 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
     // the records of this step have landed once at most the later requests are outstanding
     wait_vm_upto(per_tile * max(0, issued - PER * (s + 1)));
     raw_barrier();  // ... for every wavefront; and every wavefront is done with the previous step's slots
+    // The requests of this step (the slots freed by the barrier) are not issued here in one
+    // burst: right after a barrier all eight wavefronts would queue at the CU's one vector
+    // memory port (about 16 cycles per 1 KB instruction).  A wavefront with a tile to multiply
+    // spreads them over its first contraction; the others issue them at once.
+    constexpr int NDMA = PER * (NFULL + 1);  // instruction slots per step: per record NFULL full ones and the tail
+    int dib[PER];  // query block requested for slot sc + NB - PER + k, or -1 (wave-uniform)
 #pragma unroll
-    for (int k = NB - PER; k < NB; ++k) {
+    for (int k = 0; k < PER; ++k) {
       bool mk = false;
-      const int ib = walk.next(mk);
-      if (ib >= 0) {
-        issue(ib, modnb(sc + k));
-        pending |= (mk ? 1u : 0u) << k;
+      dib[k] = walk.next(mk);
+      if (dib[k] >= 0) {
+        pending |= (mk ? 1u : 0u) << (NB - PER + k);
         ++issued;
       }
     }
+    auto emit = [&](int q) {  // the q-th instruction slot; every wavefront keeps the same order
+      const int k = q / (NFULL + 1), n = q % (NFULL + 1);
+      if (dib[k] < 0) return;
+      const uint8_t* src = ws + dib[k] * (int64_t)R::BYTES + tid * 16 + n * (NT * 16);
+      uint8_t* dst = ring + modnb(sc + NB - PER + k) * R::BYTES + wave * 1024 + n * (NT * 16);
+      if (n < NFULL) dma16(src, dst);
+      else if (NTAIL && wave == 0 && lane < NTAIL) dma16(src, dst);
+    };
     const int kpos = NQT == 1 ? par : 0;
     const bool mine = (pending >> kpos) & 1u;
     pending >>= PER;
+    constexpr bool SPREAD = NQT == 1;  // (with two query sub-tiles the spread costs registers the kernel does not have)
+    if (!SPREAD || !mine) {
+#pragma unroll
+      for (int q = 0; q < NDMA; ++q) emit(q);
+    }
     if (mine) {
       const uint8_t* rb = ring + modnb(sc + kpos) * R::BYTES;
       const uint8_t* Qc = rb + R::QC;
@@ -1025,13 +1043,17 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
       f32x16 sacc, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[r] = dp[r] = 0.f;
+      static_assert(!SPREAD || NDMA <= DS, "one DMA slot per k-step of the first contraction");
 #pragma unroll
       for (int f = 0; f < 4 * DS; f += 2) {
         if (f & 2) dp = mfma32(fr[f % RING], fr[(f + 1) % RING], dp);
         else sacc = mfma32(fr[f % RING], fr[(f + 1) % RING], sacc);
         if (f + RING < NF) fr[f % RING] = frag(f + RING);
         if (f + 1 + RING < NF) fr[(f + 1) % RING] = frag(f + 1 + RING);
-        if (f & 2) BSA_FENCE();
+        if (f & 2) {
+          if (SPREAD && (f >> 2) < NDMA) emit(f >> 2);
+          BSA_FENCE();
+        }
       }
       // D layout: lane = key column, register r = query row 32*qt + 8*(r/4) + 4*grp + r%4
 #pragma unroll
