@@ -197,19 +197,21 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
 
   // DMA plan of this thread: LDS slot (tid + NT n) of a tile is position p of row r and
   // receives chunk p ^ swz<D>(r) of that row from global memory.
-  int goff[NI];
+  uint32_t goff[NI];  // bytes, relative to the block origin
 #pragma unroll
   for (int n = 0; n < NI; ++n) {
     const int slot = tid + NT * n, r = slot / CPR, c = (slot % CPR) ^ swz<D>(r);
-    goff[n] = koff[r] * D + c * 8;
+    goff[n] = (uint32_t)(koff[r] * D + c * 8) * 2u;
   }
-  auto issue = [&](int jb, int b) {
+  const uint32_t lds_wave = uniform_lds(ring + wave * 1024);
+  auto issue = [&](int jb, int b) {  // addresses: scalar base of the block + the lane's offset; nothing vector per instruction
     const int64_t origin = (int64_t)block_origin_fast(g, jb) * D;
-    uint8_t* kdst = ring + b * 2 * TILE + wave * 1024;
+    const uint64_t kbase = uniform64(Kh + origin), vbase = uniform64(Vh + origin);
+    const uint32_t kdst = lds_wave + b * 2 * TILE;
 #pragma unroll
-    for (int n = 0; n < NI; ++n) dma16(Kh + origin + goff[n], kdst + n * (NT * 16));
+    for (int n = 0; n < NI; ++n) dma16_raw(kbase, goff[n], kdst + n * (NT * 16));
 #pragma unroll
-    for (int n = 0; n < NI; ++n) dma16(Vh + origin + goff[n], kdst + TILE + n * (NT * 16));
+    for (int n = 0; n < NI; ++n) dma16_raw(vbase, goff[n], kdst + TILE + n * (NT * 16));
   };
 
   // Q^T fragments (B operand): lane (col, grp) holds channels 16 s + 8 grp .. +7 of its query
@@ -634,19 +636,21 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
       }
     }
   }
-  int goff[NI];
+  uint32_t goff[NI];  // bytes, relative to the block origin
 #pragma unroll
   for (int n = 0; n < NI; ++n) {
     const int slot = tid + NT * n, r = slot / CPR, c = (slot % CPR) ^ swz<D>(r);
-    goff[n] = koff[r] * D + c * 8;
+    goff[n] = (uint32_t)(koff[r] * D + c * 8) * 2u;
   }
-  auto issue = [&](int jb, int b) {
+  const uint32_t lds_wave = uniform_lds(ring + wave * 1024);
+  auto issue = [&](int jb, int b) {  // addresses: scalar base of the block + the lane's offset; nothing vector per instruction
     const int64_t origin = (int64_t)block_origin_fast(g, jb) * D;
-    uint8_t* kdst = ring + b * 2 * TILE + wave * 1024;
+    const uint64_t kbase = uniform64(Kh + origin), vbase = uniform64(Vh + origin);
+    const uint32_t kdst = lds_wave + b * 2 * TILE;
 #pragma unroll
-    for (int n = 0; n < NI; ++n) dma16(Kh + origin + goff[n], kdst + n * (NT * 16));
+    for (int n = 0; n < NI; ++n) dma16_raw(kbase, goff[n], kdst + n * (NT * 16));
 #pragma unroll
-    for (int n = 0; n < NI; ++n) dma16(Vh + origin + goff[n], kdst + TILE + n * (NT * 16));
+    for (int n = 0; n < NI; ++n) dma16_raw(vbase, goff[n], kdst + TILE + n * (NT * 16));
   };
 
   // Q^T and G^T fragments (B operands) and the row constants, from the query block's record

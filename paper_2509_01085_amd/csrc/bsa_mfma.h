@@ -104,6 +104,25 @@ __device__ inline void dma16(const void* gsrc, void* lds_wave_base) {
                : "memory", "m0");
 }
 
+// The same with every wave-uniform part already in scalar registers: a 64-bit scalar base,
+// a 32-bit per-lane byte offset and the LDS address.  No vector arithmetic per instruction.
+// (readfirstlane returns a signed int: each half is widened as unsigned, or a low half with
+// bit 31 set would sign-extend over the high half.)
+__device__ inline uint64_t uniform64(const void* p) {
+  const uint64_t b = (uint64_t)(uintptr_t)p;
+  return ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32)) << 32) |
+         (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b);
+}
+__device__ inline uint32_t uniform_lds(void* p) {
+  return (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)p);
+}
+__device__ inline void dma16_raw(uint64_t sbase, uint32_t lane_offset, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_offset), "s"(sbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+
 // Barrier without the memory fence of __syncthreads() (see dma16): callers pair it with
 // explicit waits.  The empty asm statements stop the compiler moving LDS accesses across it.
 __device__ inline void raw_barrier() {
