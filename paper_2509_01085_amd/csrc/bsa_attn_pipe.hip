@@ -972,6 +972,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
     if (NTAIL && wave == 0 && lane < NTAIL) dma16(src + NFULL * (NT * 16), dst + NFULL * (NT * 16));
   };
   auto modnb = [](int x) { return x >= NB ? x - NB : x; };
+  const uint32_t lds_wave = uniform_lds(ring + wave * 1024), tid16 = tid * 16u;
   Walk2 walk(masks, W, which);
   int issued = 0;        // records requested so far (positions of the union walk)
   uint32_t pending = 0;  // bit k: position PER*s + k is on this wavefront's list
@@ -1008,10 +1009,10 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
     auto emit = [&](int q) {  // the q-th instruction slot; every wavefront keeps the same order
       const int k = q / (NFULL + 1), n = q % (NFULL + 1);
       if (dib[k] < 0) return;
-      const uint8_t* src = ws + dib[k] * (int64_t)R::BYTES + tid * 16 + n * (NT * 16);
-      uint8_t* dst = ring + modnb(sc + NB - PER + k) * R::BYTES + wave * 1024 + n * (NT * 16);
-      if (n < NFULL) dma16(src, dst);
-      else if (NTAIL && wave == 0 && lane < NTAIL) dma16(src, dst);
+      const uint64_t src = uniform64(ws + dib[k] * (int64_t)R::BYTES + n * (NT * 16));  // scalar; the lane adds tid * 16
+      const uint32_t dst = lds_wave + modnb(sc + NB - PER + k) * R::BYTES + n * (NT * 16);
+      if (n < NFULL) dma16_raw(src, tid16, dst);
+      else if (NTAIL && wave == 0 && lane < NTAIL) dma16_raw(src, tid16, dst);
     };
     const int kpos = NQT == 1 ? par : 0;
     const bool mine = (pending >> kpos) & 1u;
