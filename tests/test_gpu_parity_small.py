@@ -214,3 +214,51 @@ def test_block_major_layout_is_a_pure_permutation_of_the_raster_results(raster, 
     for name in ("O", "dQ", "dK", "dV"):
         assert torch.equal(a[name][:, :, order], b[name]), name
     assert torch.equal(a["LSE"][:, :, order], b["LSE"])
+
+
+def test_whole_step_is_graph_capturable_and_replays_bit_identically():
+    """The library allocates nothing, never synchronises and launches only kernels: one layer
+    (all five calls, caller-owned buffers) is captured into a HIP graph; every replay, with
+    eager work and synchronisations in between, must reproduce the eager results bit for bit."""
+    wl = CASES["win_split"]
+    shp = U.shape_of(wl)
+    x = U.device_inputs(wl)
+    dev = x["Q"].device
+    nk = B.n_keep(shp, wl.keep_ratio)
+    Qbar = torch.empty((wl.B, wl.H, shp.N, wl.d), dtype=torch.float64, device=dev)
+    Kbar = torch.empty_like(Qbar)
+    lists = B.alloc_kv_lists(shp, dev)
+    keep = torch.empty((wl.B, wl.H, shp.N, nk), dtype=torch.int32, device=dev)
+    O, dQ, dK, dV = (torch.empty_like(x["Q"]) for _ in range(4))
+    LSE = torch.empty((wl.B, wl.H, wl.L), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(1, B.bwd_workspace_bytes(shp, nk)), dtype=torch.uint8, device=dev)
+    fws = torch.empty(max(1, B.fwd_workspace_bytes(shp, nk)), dtype=torch.uint8, device=dev)
+
+    def step():
+        B.pool_blocks(shp, x["Q"], Qbar)
+        B.pool_blocks(shp, x["K"], Kbar)
+        B.select_kv(shp, Qbar, Kbar, wl.threshold, out=lists)
+        B.prune_q(shp, x["Q"], wl.keep_ratio, keep)
+        B.attn_fwd(shp, x["Q"], x["K"], x["V"], lists, keep, O=O, LSE=LSE, workspace=fws)
+        B.attn_bwd(shp, x["Q"], x["K"], x["V"], O, LSE, x["dO"], lists, keep, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (O, LSE, dQ, dK, dV, lists.q2k_ptr, lists.k2q_ptr, keep)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up on the capture stream, as torch asks
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in (O, LSE, dQ, dK, dV, keep):
+            t.zero_()  # eager work between the replays
+        lists.q2k_ptr.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b_ in zip(ref, (O, LSE, dQ, dK, dV, lists.q2k_ptr, lists.k2q_ptr, keep)):
+            assert torch.equal(a, b_), rep
