@@ -298,11 +298,22 @@ def main():
     kernels = {"fwd_pipe_kernel": ("attn_fwd", 4), "bwd_dkv_pipe_kernel": ("bwd_dkv", 8), "bwd_dq_pipe_kernel": ("bwd_dq", 2)}
     dominant = max(kernels, key=lambda k: parts[kernels[k][0]])
 
+    # second denominator: what a register-resident MFMA loop sustains on this GPU (two workgroups per CU)
+    sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+    B.mfma_probe(512, 2000, sink)
+    probe_flops = [0]
+
+    def probe():
+        probe_flops[0] = B.mfma_probe(512, 20000, sink)
+
+    t_probe = timed(torch, probe, 3)
+    probe_tflops = probe_flops[0] / (t_probe * 1e-3) / 1e12
+
     def roof(kname):
         call, mult = kernels[kname]
         tf = mult * pair_flops / (parts[call] * 1e-3) / 1e12
         return {"kernel": kname, "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": tf / PEAK_BF16_TFLOPS,
+                "frac": tf / PEAK_BF16_TFLOPS, "frac_of_measured_mfma_loop": tf / probe_tflops,
                 "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, kname)) if not over else None, "avg_launch_ms": parts[call],
                 "algorithmic_flops_per_launch": mult * pair_flops}
 
@@ -321,6 +332,11 @@ def main():
         "roofline": roof(dominant),
         "roofline_other": [roof(k) for k in kernels if k != dominant],
         "wall_s_timed_region": wall,
+        "mfma_loop_measured_tflops": probe_tflops,
+        "memory": {"torch_max_allocated_bytes": int(torch.cuda.max_memory_allocated()),
+                   "bwd_workspace_bytes": int(ws.numel()), "fwd_workspace_bytes": int(fws.numel()),
+                   "kv_list_capacity_bytes": int(sum(t.numel() * t.element_size() for t in (lists.q2k_ptr, lists.q2k_idx, lists.k2q_ptr, lists.k2q_idx))),
+                   "select_workspace_bytes": int(lists.workspace.numel())},
     }
     pool_bytes = 2 * Q.numel() * Q.element_size() + 2 * Qbar.numel() * 8 + keep.numel() * 4 + Q.numel() * Q.element_size()
     t_stream = parts["pool_q"] + parts["pool_k"] + parts["prune"]

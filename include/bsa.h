@@ -200,6 +200,17 @@ int bsa_dense_attn_bwd(const bsa_shape_t* shape, const void* Q, const void* K, c
                        void* dQ, void* dK, void* dV,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid, not a step of the method: launches `workgroups` workgroups of four
+ * wavefronts that each run `iters` rounds of four independent 32 x 32 x 16 bf16 matrix-core
+ * products with operands and accumulators held in registers, and returns the number of
+ * floating-point operations the launch performs (negative: an error code).  Timed by the
+ * caller, it gives the matrix-core rate this GPU sustains with no memory traffic at all: the
+ * second denominator (beside the published peak) for the attention kernels' achieved rates.
+ * `sink` is a device array of workgroups * 256 floats that receives one value per thread.
+ */
+int64_t bsa_mfma_probe(int workgroups, int iters, float* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ RASTER, BLOCK_MAJOR = 0, 1
 EXPORTS = (
     "bsa_strerror", "bsa_n_keep", "bsa_pool_blocks", "bsa_select_workspace_bytes", "bsa_select_kv",
     "bsa_select_kv_stat", "bsa_prune_q", "bsa_fwd_workspace_bytes", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd", "bsa_attn_bwd_stages",
-    "bsa_dense_bwd_workspace_bytes", "bsa_dense_attn_fwd", "bsa_dense_attn_bwd",
+    "bsa_dense_bwd_workspace_bytes", "bsa_dense_attn_fwd", "bsa_dense_attn_bwd", "bsa_mfma_probe",
 )
 
 
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
         L.bsa_dense_attn_fwd.argtypes = [P, vp, vp, vp, f32, vp, vp, vp]
         L.bsa_dense_attn_bwd.restype = C.c_int
         L.bsa_dense_attn_bwd.argtypes = [P] + [vp] * 6 + [f32, vp, vp, vp, vp, sz, vp]
+        L.bsa_mfma_probe.restype, L.bsa_mfma_probe.argtypes = i64, [i32, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -286,3 +287,15 @@ def dense_attn_bwd(shape: Shape, Q, K, V, O, LSE, dO, sm_scale: Optional[float] 
                                   sm_scale, _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), workspace.numel(), _stream())
     _check(st, "bsa_dense_attn_bwd")
     return dQ, dK, dV
+
+
+def mfma_probe(workgroups: int, iters: int, sink=None) -> int:
+    """Enqueue the register-resident matrix-core loop; returns the flops the launch performs."""
+    if sink is None:
+        sink = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    if sink.numel() < workgroups * 256:
+        raise ValueError("sink too small")
+    flops = lib().bsa_mfma_probe(workgroups, iters, _ptr(sink), _stream())
+    if flops < 0:
+        _check(int(flops), "bsa_mfma_probe")
+    return int(flops)

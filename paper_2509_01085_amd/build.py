@@ -17,6 +17,7 @@ SOURCES = [
     "bsa_select.hip",
     "bsa_attn_generic.hip",
     "bsa_attn_pipe.hip",
+    "bsa_probe.hip",
 ]
 # -ffp-contract=off: the decision kernels fix every rounding; packed-fp32 ops are disabled
 # on the test machines (some forms have produced wrong results).

@@ -96,3 +96,6 @@ def test_null_range_capacity_workspace_errors_come_before_any_launch():
     assert lib.bsa_dense_attn_fwd(s, p, p, None, 0.125, p, p, None) == -1
     dws = B.dense_bwd_workspace_bytes(GOOD)
     assert lib.bsa_dense_attn_bwd(s, *([p] * 6), 0.125, p, p, p, p, dws - 1, None) == -7
+    # the matrix-core probe checks its arguments before it launches anything
+    assert lib.bsa_mfma_probe(1, 1, None, None) == -1
+    assert lib.bsa_mfma_probe(0, 1, p, None) == -3 and lib.bsa_mfma_probe(1, 0, p, None) == -3
