@@ -334,7 +334,7 @@ def main():
         "wall_s_timed_region": wall,
         "mfma_loop_measured_tflops": probe_tflops,
         "memory": {"torch_max_allocated_bytes": int(torch.cuda.max_memory_allocated()),
-                   "bwd_workspace_bytes": int(ws.numel()), "fwd_workspace_bytes": int(fws.numel()),
+                   "bwd_workspace_bytes": int(B.bwd_workspace_bytes(shp, nk)), "fwd_workspace_bytes": int(B.fwd_workspace_bytes(shp, nk)),
                    "kv_list_capacity_bytes": int(sum(t.numel() * t.element_size() for t in (lists.q2k_ptr, lists.q2k_idx, lists.k2q_ptr, lists.k2q_idx))),
                    "select_workspace_bytes": int(lists.workspace.numel())},
     }
