@@ -19,8 +19,8 @@ SELECT_MARGIN = 1e-10
 
 
 def progress(msg: str) -> None:
-    """Progress line of a long test: stdout (visible with -s) and a file under gpurun_out/,
-    so that a run whose output pytest captures is still seen to be alive."""
+    """Progress line of a long test: stdout (visible with -s) and a log file in the run's output
+    folder, so that a run whose output pytest captures is still seen to be alive."""
     import os
     import time
 
