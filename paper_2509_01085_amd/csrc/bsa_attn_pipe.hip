@@ -27,12 +27,6 @@ bool mfma_supported(const Geom& g, int dtype, int n_keep) {
   return dtype == BSA_BF16 && g.Bk == PBK && (g.d == 128 || g.d == 64) && n_keep <= PBK;
 }
 
-__device__ inline int xcd_remap8(int n, int total) {
-  // workgroup n runs on XCD n % 8; give every XCD one contiguous range of units
-  const int q = total >> 3, r = total & 7, x = n & 7;
-  return x * q + min(x, r) + (n >> 3);
-}
-
 // ---- work items -------------------------------------------------------------------------
 // A launch covers `units` units of work (four query blocks of a head each).  Workgroups are
 // dispatched round-robin over the 8 XCDs, so XCD x is given the contiguous unit range
@@ -40,7 +34,8 @@ __device__ inline int xcd_remap8(int n, int total) {
 // lists overlap, share that XCD's L2.  When the launch is only a few rounds long (units per
 // workgroup slot), its tail leaves most of the chip idle; then the last split_n units of every
 // XCD's range are walked in split_S segments by separate, shorter workgroups dispatched last,
-// and a combine launch merges their partial results.
+// and a combine launch merges their partial results.  The dK/dV launch (units = pairs of KV
+// blocks, one workgroup per CU) does the same for the units of its last, partly filled round.
 constexpr int kCUs = 256;  // compute units of the MI355X
 
 
@@ -838,19 +833,40 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
 // ------------------------------------------------------------------------------ dK, dV
 struct Walk2 {  // ascending walk over the union of two lists (bit masks in LDS), scalar state
   const uint32_t* masks;  // [2][W]
-  int W, own_list, word;
+  int W, own_list, word, left;
   uint32_t u, own;
-  __device__ inline Walk2(const uint32_t* m, int W_, int own_) : masks(m), W(W_), own_list(own_), word(-1), u(0), own(0) {}
+  __device__ inline Walk2(const uint32_t* m, int W_, int own_)
+      : masks(m), W(W_), own_list(own_), word(-1), left(0x7fffffff), u(0), own(0) {}
+  __device__ inline void load() {
+    u = __builtin_amdgcn_readfirstlane(masks[word] | masks[W + word]);
+    own = __builtin_amdgcn_readfirstlane(masks[own_list * W + word]);
+  }
   __device__ inline int next(bool& mine) {
+    if (left <= 0) return -1;
     while (u == 0) {
       if (++word >= W) return -1;
-      u = __builtin_amdgcn_readfirstlane(masks[word] | masks[W + word]);
-      own = __builtin_amdgcn_readfirstlane(masks[own_list * W + word]);
+      load();
     }
     const int b = __builtin_ctz(u);
     u &= u - 1;
     mine = (own >> b) & 1u;
+    --left;
     return word * 32 + b;
+  }
+  // restrict a fresh walk to segment `seg` of `nseg` equal parts of the union
+  __device__ inline void restrict_to(int seg, int nseg) {
+    int total = 0;
+    for (int w = 0; w < W; ++w) total += __builtin_popcount(__builtin_amdgcn_readfirstlane(masks[w] | masks[W + w]));
+    int skip = (int)((int64_t)seg * total / nseg);
+    left = (int)((int64_t)(seg + 1) * total / nseg) - skip;
+    while (++word < W) {
+      load();
+      const int c = __builtin_popcount(u);
+      if (skip < c) break;
+      skip -= c;
+      u = 0;
+    }
+    for (; skip > 0; --skip) u &= u - 1;
   }
 };
 
@@ -897,7 +913,9 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
   const int grp = lane >> 5, col = lane & 31;
   const int par = wave >> 2, which = (wave >> 1) & 1, half = wave & 1;
   const int npairs = (g.N + 1) / 2;
-  const int unit = xcd_remap8(blockIdx.x, gridDim.x);
+  Item it;
+  if (!item_of(blockIdx.x, npairs * g.B * g.H, a.kv_split_S, a.kv_split_n, it)) return;
+  const int unit = it.unit;
   const int64_t bh = unit / npairs;
   const int j0 = (unit % npairs) * 2;
   const int j = j0 + which;  // this wavefront's KV block; it owns keys 32*half .. +31
@@ -974,6 +992,7 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
   auto modnb = [](int x) { return x >= NB ? x - NB : x; };
   const uint32_t lds_wave = uniform_lds(ring + wave * 1024), tid16 = tid * 16u;
   Walk2 walk(masks, W, which);
+  if (it.nseg > 1) walk.restrict_to(it.seg, it.nseg);
   int issued = 0;        // records requested so far (positions of the union walk)
   uint32_t pending = 0;  // bit k: position PER*s + k is on this wavefront's list
 #pragma unroll
@@ -1114,6 +1133,22 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
         }
     }
   }
+  if (it.sidx >= 0) {  // a segment of a split unit: leave the raw sums for the combine launch
+    if (par == 0) {
+      f32x4* part = reinterpret_cast<f32x4*>(a.kv_part) +
+                    (((int64_t)it.sidx * a.kv_split_S + it.seg) * 4 + (wave & 3)) * (2 * DT * 4 * 64) + lane;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          f32x4 kq = {dk[dt][4 * r4], dk[dt][4 * r4 + 1], dk[dt][4 * r4 + 2], dk[dt][4 * r4 + 3]};
+          f32x4 vq = {dv[dt][4 * r4], dv[dt][4 * r4 + 1], dv[dt][4 * r4 + 2], dv[dt][4 * r4 + 3]};
+          __builtin_nontemporal_store(kq, part + (dt * 4 + r4) * 64);
+          __builtin_nontemporal_store(vq, part + (DT * 4 + dt * 4 + r4) * 64);
+        }
+    }
+    return;
+  }
   if (valid && par == 0) {
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -1131,6 +1166,53 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
   }
 }
 
+// Finishes the split units of the dK/dV launch: sums the segments' partial results in segment
+// order and stores dK, dV.  Four wavefronts = (KV block of the pair, key half), laid out as the
+// main kernel's parity-0 wavefronts.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_dkv_combine_kernel(Geom g, AttnArgs a) {
+  constexpr int DT = D / 32, NV = 2 * DT * 4;  // float4 values per lane: dK then dV
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int grp = lane >> 5, col = lane & 31;
+  const int which = wave >> 1, half = wave & 1;
+  const int npairs = (g.N + 1) / 2;
+  const Item it = split_item_of(blockIdx.x, npairs * g.B * g.H, a.kv_split_S, a.kv_split_n);
+  const int64_t bh = it.unit / npairs;
+  const int j = (it.unit % npairs) * 2 + which;
+  if (j >= g.N) return;
+  const f32x4* part = reinterpret_cast<const f32x4*>(a.kv_part) + ((int64_t)it.sidx * a.kv_split_S * 4 + wave) * (NV * 64) + lane;
+  f32x4 acc[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) acc[v] = __builtin_nontemporal_load(part + v * 64);
+  for (int sgm = 1; sgm < a.kv_split_S; ++sgm) {
+    const f32x4* ps = part + (int64_t)sgm * 4 * (NV * 64);
+    f32x4 t[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) t[v] = __builtin_nontemporal_load(ps + v * 64);
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[v][e] += t[v][e];
+  }
+  const int64_t ktok = block_origin(g, j) + intra_offset(g, 32 * half + col);
+  uint16_t* dKh = static_cast<uint16_t*>(a.dK) + bh * g.L * D;
+  uint16_t* dVh = static_cast<uint16_t*>(a.dV) + bh * g.L * D;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const f32x4 kq = acc[dt * 4 + r4], vq = acc[DT * 4 + dt * 4 + r4];
+      u32x2 kv, vv;
+      kv.x = pack_bf16(kq[0] * a.sm_scale, kq[1] * a.sm_scale);
+      kv.y = pack_bf16(kq[2] * a.sm_scale, kq[3] * a.sm_scale);
+      vv.x = pack_bf16(vq[0], vq[1]);
+      vv.y = pack_bf16(vq[2], vq[3]);
+      const int ch = 32 * dt + 8 * r4 + 4 * grp;
+      *reinterpret_cast<u32x2*>(dKh + ktok * D + ch) = kv;
+      *reinterpret_cast<u32x2*>(dVh + ktok * D + ch) = vv;
+    }
+}
+
 // floats per lane of one wavefront's partial result
 constexpr int fwd_part_regs(int d) { return (d / 32) * 16 + 2; }
 constexpr int dq_part_regs(int d) { return (d / 32) * 16; }
@@ -1139,6 +1221,21 @@ static SplitPlan fwd_plan(const Geom& g, int n_keep, bool allow) {
   const bool splitq = n_keep > 32;
   return plan_split(((g.N + PG - 1) / PG) * g.B * g.H, kCUs * (splitq ? 1 : 2), allow);
 }
+
+// dK/dV: one workgroup per CU and many rounds, so only the units of the last, partly filled
+// round of every XCD (and a few more, against the spread of the unit lengths) are split.
+static SplitPlan dkv_plan(const Geom& g) {
+  const int units = ((g.N + 1) / 2) * g.B * g.H, q = units / 8, r = units % 8, per_xcd = kCUs / 8;
+  SplitPlan p{1, 0, 0, 0};
+  if (!g.dense && q >= 4 && q < 64 * per_xcd) {
+    p.S = 4;
+    p.n = min(q % per_xcd + per_xcd / 4, q / 2);
+  }
+  p.grid = 8 * (q + (r ? 1 : 0) - p.n + p.S * p.n);
+  p.units = 8 * p.n;
+  return p;
+}
+constexpr size_t dkv_part_bytes(int d) { return (size_t)4 * 2 * (d / 32) * 16 * 64 * sizeof(float); }  // per segment
 
 template <int D, int NQT>
 static int launch_bwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
@@ -1163,8 +1260,16 @@ static int launch_bwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
     if (p.units)
       hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ, true>), dim3(p.units), dim3(SPLITQ ? 512 : 256), 0, st, g, a);
   }
-  if (a.stages & BSA_BWD_DKV)
-    hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D, NQT>), dim3(((g.N + 1) / 2) * g.B * g.H), dim3(512), lds_kv, st, g, a);
+  if (a.stages & BSA_BWD_DKV) {
+    const SplitPlan p = dkv_plan(g);
+    const SplitPlan pq = fwd_plan(g, a.n_keep, !g.dense);
+    a.kv_split_S = p.S;
+    a.kv_split_n = p.n;
+    a.kv_part = reinterpret_cast<float*>(static_cast<uint8_t*>(a.ws) + (size_t)R::BYTES * g.rows +
+                                         (size_t)pq.units * pq.S * (SPLITQ ? 8 : 4) * dq_part_regs(D) * 64 * sizeof(float));
+    hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D, NQT>), dim3(p.grid), dim3(512), lds_kv, st, g, a);
+    if (p.units) hipLaunchKernelGGL((bwd_dkv_combine_kernel<D>), dim3(p.units), dim3(256), 0, st, g, a);
+  }
   return check_launch();
 }
 
@@ -1180,7 +1285,8 @@ size_t bwd_workspace_pipe(const Geom& g, int n_keep) {
                                     : (two ? BwdRec<64, 2>::BYTES : BwdRec<64, 1>::BYTES);
   const SplitPlan p = fwd_plan(g, n_keep, !g.dense);
   const size_t partials = (size_t)p.units * p.S * (two ? 8 : 4) * dq_part_regs(g.d) * 64 * sizeof(float);
-  return per_row * (size_t)g.rows + partials;
+  const SplitPlan pk = dkv_plan(g);
+  return per_row * (size_t)g.rows + partials + (size_t)pk.units * pk.S * dkv_part_bytes(g.d);  // records | dQ partials | dK/dV partials
 }
 
 size_t fwd_workspace_pipe(const Geom& g, int n_keep) {

@@ -118,6 +118,8 @@ struct AttnArgs {
   int split_S, split_n;
   float* part;
   void* fwd_ws;
+  int kv_split_S, kv_split_n;  // the same for the dK/dV launch
+  float* kv_part;
 };
 
 // plain-ALU fp32-accumulate kernels: any supported shape, fp32 or bf16 storage
