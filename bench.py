@@ -30,9 +30,9 @@ PEAK_HBM_GBS = 8000.0
 # (FETCH_SIZE, WRITE_SIZE, scaled by a 1 GiB copy's readings) recorded in profiles/bench_<workload>.md.
 # Hardware counters cannot be read from inside this process, so the figure is carried here.
 MEASURED_TRAFFIC_BYTES = {
-    ("wan1p3b", "bwd_dkv_pipe_kernel"): 3.62e9,
-    ("wan1p3b", "bwd_dq_pipe_kernel"): 10.65e9,
-    ("wan1p3b", "fwd_pipe_kernel"): 9.89e9,
+    ("wan1p3b", "bwd_dkv_pipe_kernel"): 3.77e9,
+    ("wan1p3b", "bwd_dq_pipe_kernel"): 10.67e9,
+    ("wan1p3b", "fwd_pipe_kernel"): 9.87e9,
 }
 
 
