@@ -341,6 +341,11 @@ def main():
     pool_bytes = 2 * Q.numel() * Q.element_size() + 2 * Qbar.numel() * 8 + keep.numel() * 4 + Q.numel() * Q.element_size()
     t_stream = parts["pool_q"] + parts["pool_k"] + parts["prune"]
     out["index_prep_hbm"] = {"bytes": pool_bytes, "achieved_GBs": pool_bytes / (t_stream * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS}
+    # selection: reads the pooled vectors, writes the CSR and its transpose; nominally HBM, in practice fp64 ALU work
+    sel_bytes = 2 * Qbar.numel() * 8 + 2 * nnz * 4 + 2 * (shp.rows + 1) * 4
+    out["select_hbm"] = {"bytes": sel_bytes, "achieved_GBs": sel_bytes / (parts["select"] * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
+                         "pct_of_layer_time": 100.0 * parts["select"] / ms_step,
+                         "fp64_gflop": 2.0 * shp.rows * shp.N * wl.d / 1e9}
 
     if not args.no_dense and wl.L <= 40000:
         dws = torch.empty(max(1, B.dense_bwd_workspace_bytes(shp)), dtype=torch.uint8, device=dev)
