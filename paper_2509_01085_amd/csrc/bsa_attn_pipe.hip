@@ -83,21 +83,29 @@ __device__ inline Item split_item_of(int b, int units, int S, int n) {
   return it;
 }
 
-// Ascending walk over the union of four block lists kept as bit masks in LDS.  Every value
+// Ascending walk over the union of NL block lists kept as bit masks in LDS.  Every value
 // is wave-uniform; readfirstlane moves the words to scalar registers so the bit scanning
 // costs scalar, not vector, instructions.
-struct Walk4 {
-  const uint32_t* masks;  // [4][W]
+template <int NL, int NOWN>
+struct WalkN {
+  const uint32_t* masks;  // [NL][W]
   int W, own_list, word, left;
-  uint32_t u, own;
-  __device__ inline Walk4(const uint32_t* m, int W_, int own_)
-      : masks(m), W(W_), own_list(own_), word(-1), left(0x7fffffff), u(0), own(0) {}
-  __device__ inline void load() {
-    const uint32_t all = masks[word] | masks[W + word] | masks[2 * W + word] | masks[3 * W + word];
-    u = __builtin_amdgcn_readfirstlane(all);
-    own = __builtin_amdgcn_readfirstlane(masks[own_list * W + word]);
+  uint32_t u, own, own2;  // own, own2: the wavefront's own list(s), NOWN of them, own_list and own_list + 1
+  __device__ inline WalkN(const uint32_t* m, int W_, int own_)
+      : masks(m), W(W_), own_list(own_), word(-1), left(0x7fffffff), u(0), own(0), own2(0) {}
+  __device__ inline uint32_t any(int w) const {
+    uint32_t all = masks[w];
+#pragma unroll
+    for (int k = 1; k < NL; ++k) all |= masks[k * W + w];
+    return all;
   }
-  __device__ inline int next(bool& mine) {
+  __device__ inline void load() {
+    u = __builtin_amdgcn_readfirstlane(any(word));
+    own = __builtin_amdgcn_readfirstlane(masks[own_list * W + word]);
+    if (NOWN == 2) own2 = __builtin_amdgcn_readfirstlane(masks[(own_list + 1) * W + word]);
+  }
+  // next tile of the union; mine: bit 0 = on the first own list, bit 1 = on the second
+  __device__ inline int next(uint32_t& mine) {
     if (left <= 0) return -1;
     while (u == 0) {
       if (++word >= W) return -1;
@@ -105,17 +113,20 @@ struct Walk4 {
     }
     const int b = __builtin_ctz(u);
     u &= u - 1;
-    mine = (own >> b) & 1u;
+    mine = ((own >> b) & 1u) | (NOWN == 2 ? ((own2 >> b) & 1u) << 1 : 0u);
     --left;
     return word * 32 + b;
+  }
+  __device__ inline int next(bool& mine) {
+    uint32_t m = 0;
+    const int r = next(m);
+    mine = m != 0;
+    return r;
   }
   // restrict a fresh walk to segment `seg` of `nseg` equal parts of the union
   __device__ inline void restrict_to(int seg, int nseg) {
     int total = 0;
-    for (int w = 0; w < W; ++w) {
-      const uint32_t all = masks[w] | masks[W + w] | masks[2 * W + w] | masks[3 * W + w];
-      total += __builtin_popcount(__builtin_amdgcn_readfirstlane(all));
-    }
+    for (int w = 0; w < W; ++w) total += __builtin_popcount(__builtin_amdgcn_readfirstlane(any(w)));
     int skip = (int)((int64_t)seg * total / nseg);
     left = (int)((int64_t)(seg + 1) * total / nseg) - skip;
     while (++word < W) {
@@ -135,8 +146,13 @@ struct Walk4 {
 // COMBINE = false: the walk (a whole unit, or one segment of a split unit, whose unnormalised
 // accumulators, running maxima and sums go to a.part).  COMBINE = true: merge the segments of
 // a split unit and finish it.  Both end in the same epilogue.
-template <int D, bool SPLITQ, bool COMBINE>
+// PACK (n_keep <= 16): a wavefront carries two query blocks, 16 columns of its 32-column MFMA
+// tile each, so a workgroup covers eight blocks; a tile that only one of the two lists holds
+// is masked (-inf) in the other block's columns.
+template <int D, bool SPLITQ, bool COMBINE, bool PACK>
 __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g, AttnArgs a) {
+  static_assert(!(PACK && SPLITQ), "packing is for short retained sets");
+  constexpr int PG = PACK ? 2 * bsa::PG : bsa::PG;  // query blocks per workgroup
   constexpr int NT = SPLITQ ? 512 : 256;  // threads
   constexpr int NB = SPLITQ ? 4 : 2;      // LDS ring depth (tiles)
   constexpr int RB = D * 2;               // bytes per tile row
@@ -153,7 +169,10 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = lane >> 5, col = lane & 31;
-  const int qb = wave & 3, sub = wave >> 2;  // sub: which 32 queries of the block (always 0 with four wavefronts)
+  const int sub = wave >> 2;                 // which 32 queries of the block (always 0 with four wavefronts)
+  const int qb0 = PACK ? 2 * wave : (wave & 3);            // the wavefront's (first) query block within the workgroup
+  const int qb = PACK ? qb0 + (col >> 4) : qb0;            // the lane's
+  constexpr int NOWN = PACK ? 2 : 1;
   constexpr int NW = NT / 64;              // wavefronts
   constexpr int NREG = (D / 32) * 16 + 2;  // floats per lane of a partial result: O^T tile, m, l
   const int ngroups = (g.N + PG - 1) / PG;
@@ -162,7 +181,8 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
   else if (!item_of(blockIdx.x, ngroups * g.B * g.H, a.split_S, a.split_n, it)) return;
   const int unit = it.unit;
   const int64_t bh = unit / ngroups;
-  const int i = (unit % ngroups) * PG + qb;  // this wavefront's query block
+  const int i0 = (unit % ngroups) * PG + qb0;  // the wavefront's first query block
+  const int i = (unit % ngroups) * PG + qb;    // the lane's query block
   const bool valid = i < g.N;
   const int64_t row = bh * g.N + i;
   const int W = (g.N + 31) / 32;
@@ -177,15 +197,21 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
     for (int k = tid; k < PG * W; k += NT) masks[k] = 0u;
   if (tid < 2 * PG) keepbits[tid >> 1][tid & 1] = 0u;
   __syncthreads();
-  if (!COMBINE && valid && sub == 0) {
-    if (g.dense) {
-      for (int w = lane; w < W; w += 64)
-        masks[qb * W + w] = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
-    } else {
-      const int beg = a.q2k_ptr[row], cnt = a.q2k_ptr[row + 1] - beg;
-      for (int t = lane; t < cnt; t += 64) {
-        const int j = a.q2k_idx[beg + t];
-        if ((unsigned)j < (unsigned)g.N) atomicOr(&masks[qb * W + (j >> 5)], 1u << (j & 31));
+  if (!COMBINE && sub == 0) {
+#pragma unroll
+    for (int o2 = 0; o2 < NOWN; ++o2) {  // the wavefront's own list(s)
+      const int ib = i0 + o2, ql = qb0 + o2;
+      if (ib >= g.N) continue;
+      if (g.dense) {
+        for (int w = lane; w < W; w += 64)
+          masks[ql * W + w] = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
+      } else {
+        const int64_t rw = bh * g.N + ib;
+        const int beg = a.q2k_ptr[rw], cnt = a.q2k_ptr[rw + 1] - beg;
+        for (int t = lane; t < cnt; t += 64) {
+          const int j = a.q2k_idx[beg + t];
+          if ((unsigned)j < (unsigned)g.N) atomicOr(&masks[ql * W + (j >> 5)], 1u << (j & 31));
+        }
       }
     }
   }
@@ -210,7 +236,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
   };
 
   // Q^T fragments (B operand): lane (col, grp) holds channels 16 s + 8 grp .. +7 of its query
-  const int qpos = 32 * sub + col;
+  const int qpos = PACK ? (col & 15) : 32 * sub + col;
   int qid = -1, qtok = 0;
   if (valid && qpos < a.n_keep) {
     qid = g.dense ? qpos : min(max(a.keep_idx[row * a.n_keep + qpos], 0), PBK - 1);
@@ -270,18 +296,18 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
         for (int r = 0; r < 16; ++r) o[dt][r] += w * v[dt * 16 + r];
     }
   }
-  Walk4 walk(masks, W, qb);  // runs NB-1 tiles ahead of the multiplication; `pending` remembers
-  int issued = 0;            // for the tiles in flight whether this wavefront's list has them
+  WalkN<PG, NOWN> walk(masks, W, qb0);  // runs NB-1 tiles ahead of the multiplication; `pending` remembers
+  int issued = 0;                      // for the tiles in flight which of this wavefront's lists have them (2 bits a tile)
   uint32_t pending = 0;
   if (!COMBINE) {
     if (it.nseg > 1) walk.restrict_to(it.seg, it.nseg);
 #pragma unroll
     for (int k = 0; k < NB - 1; ++k) {
-      bool mk = false;
+      uint32_t mk = 0;
       const int jb = walk.next(mk);
       if (jb >= 0) {
         issue(jb, k);
-        pending |= (mk ? 1u : 0u) << k;
+        pending |= mk << (2 * k);
         ++issued;
       }
     }
@@ -299,16 +325,17 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
     }
     raw_barrier();  // tile t visible to all; everyone is done with tile t-1, whose buffer is refilled now
     {
-      bool mn = false;
+      uint32_t mn = 0;
       const int jn = walk.next(mn);
       if (jn >= 0) {
         issue(jn, (t + NB - 1) & (NB - 1));
-        pending |= (mn ? 1u : 0u) << (NB - 1);
+        pending |= mn << (2 * (NB - 1));
         ++issued;
       }
     }
-    const bool mine = pending & 1u;
-    pending >>= 1;
+    const uint32_t mbits = pending & 3u;
+    const bool mine = mbits != 0;
+    pending >>= 2;
     if (mine) {
       // 64 keys x this wavefront's 32 queries.  The 4*DS A fragments of the tile (K rows for
       // both key halves, then V^T) are read from LDS through a ring of RING register
@@ -338,13 +365,21 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
         if (f + RING < NF) fr[f % RING] = frag(f + RING);
         if (f & 1) BSA_FENCE();
       }
+      if (PACK && mbits != 3u && !((mbits >> (col >> 4)) & 1u)) {  // the tile is not on this lane's block's list
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[kt][r] = -INFINITY;
+      }
       float mx = s[0][0];
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
       mx = fmaxf(mx, xor32(mx));
-      const float mnew = fmaxf(m, mx * c2);  // c2 > 0: the maximum commutes with the scaling
+      const float mtrue = fmaxf(m, mx * c2);  // c2 > 0: the maximum commutes with the scaling
+      // (packed: a query whose block has seen no tile yet stays at -inf; the arithmetic below then uses 0)
+      const float mnew = (PACK && mtrue == -INFINITY) ? 0.f : mtrue;
       const float alpha = __builtin_amdgcn_exp2f(m - mnew);
       float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
@@ -355,7 +390,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
         sum1 += s[1][r];
       }
       l = l * alpha + (sum0 + sum1);  // per-lane partial; the lane pair is summed at the end
-      m = mnew;
+      m = mtrue;
       if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {  // rescale only when some row's maximum moved
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
@@ -416,17 +451,22 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
   __syncthreads();
   // token filling: lane c of the block's first wavefront owns intra-block token c and, if it
   // was pruned, copies the row of its window's critical token
-  if (valid && !g.dense && sub == 0) {
-    const bool kept = (keepbits[qb][lane >> 5] >> (lane & 31)) & 1u;
-    const int win = window_of(g, lane);
-    const bool have = (keepbits[qb][window_center(g, win) >> 5] >> (window_center(g, win) & 31)) & 1u;
-    if (!kept && have) {
-      const int64_t tok = block_origin(g, i) + koff[lane];
-      const uint16_t* src = cen_rows + ((size_t)qb * g.nwin + win) * D;
+  if (!g.dense && sub == 0) {
 #pragma unroll
-      for (int q = 0; q < D / 8; ++q)
-        *reinterpret_cast<u32x4*>(Oh + tok * D + 8 * q) = *reinterpret_cast<const u32x4*>(src + 8 * q);
-      Lh[tok] = cen_lse[qb][win];
+    for (int o2 = 0; o2 < NOWN; ++o2) {  // the wavefront's own block(s)
+      const int ib = i0 + o2, ql = qb0 + o2;
+      if (ib >= g.N) continue;
+      const bool kept = (keepbits[ql][lane >> 5] >> (lane & 31)) & 1u;
+      const int win = window_of(g, lane);
+      const bool have = (keepbits[ql][window_center(g, win) >> 5] >> (window_center(g, win) & 31)) & 1u;
+      if (!kept && have) {
+        const int64_t tok = block_origin(g, ib) + koff[lane];
+        const uint16_t* src = cen_rows + ((size_t)ql * g.nwin + win) * D;
+#pragma unroll
+        for (int q = 0; q < D / 8; ++q)
+          *reinterpret_cast<u32x4*>(Oh + tok * D + 8 * q) = *reinterpret_cast<const u32x4*>(src + 8 * q);
+        Lh[tok] = cen_lse[ql][win];
+      }
     }
   }
 }
@@ -713,7 +753,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
         for (int r = 0; r < 16; ++r) dq[dt][r] += v[dt * 16 + r];
     }
   }
-  Walk4 walk(masks, W, qb);
+  WalkN<PG, 1> walk(masks, W, qb);
   int issued = 0;
   uint32_t pending = 0;
   if (!COMBINE) {
@@ -1217,9 +1257,12 @@ __global__ __launch_bounds__(256) void bwd_dkv_combine_kernel(Geom g, AttnArgs a
 constexpr int fwd_part_regs(int d) { return (d / 32) * 16 + 2; }
 constexpr int dq_part_regs(int d) { return (d / 32) * 16; }
 
-static SplitPlan fwd_plan(const Geom& g, int n_keep, bool allow) {
+// pack: the forward's packed variant (two query blocks per wavefront, eight per workgroup)
+static bool fwd_packs(const Geom& g, int n_keep) { return n_keep <= 16 && !g.dense; }
+static SplitPlan fwd_plan(const Geom& g, int n_keep, bool allow, bool pack = false) {
   const bool splitq = n_keep > 32;
-  return plan_split(((g.N + PG - 1) / PG) * g.B * g.H, kCUs * (splitq ? 1 : 2), allow);
+  const int pg = pack ? 2 * PG : PG;
+  return plan_split(((g.N + pg - 1) / pg) * g.B * g.H, kCUs * (splitq ? 1 : 2), allow);
 }
 
 // dK/dV: one workgroup per CU and many rounds, so only the units of the last, partly filled
@@ -1291,34 +1334,36 @@ size_t bwd_workspace_pipe(const Geom& g, int n_keep) {
 
 size_t fwd_workspace_pipe(const Geom& g, int n_keep) {
   if (g.dense) return 0;
-  const SplitPlan p = fwd_plan(g, n_keep, true);
+  const SplitPlan p = fwd_plan(g, n_keep, true, fwd_packs(g, n_keep));
   return (size_t)p.units * p.S * (n_keep > 32 ? 8 : 4) * fwd_part_regs(g.d) * 64 * sizeof(float);
 }
 
-template <int D, bool SPLITQ>
+template <int D, bool SPLITQ, bool PACK>
 static int launch_fwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
+  constexpr int PGK = PACK ? 2 * PG : PG;
   const int W = (g.N + 31) / 32;
-  const size_t lds = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PG * W * 4;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ, false>),
+  const size_t lds = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PGK * W * 4;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ, false, PACK>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
-      hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ, true>),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ, true, PACK>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
     return BSA_ERR_LAUNCH;
-  const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense && a.fwd_ws != nullptr);
+  const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense && a.fwd_ws != nullptr, PACK);
   a.split_S = p.S;
   a.split_n = p.n;
   a.part = static_cast<float*>(a.fwd_ws);
-  hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ, false>), dim3(p.grid), dim3(SPLITQ ? 512 : 256), lds, st, g, a);
+  hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ, false, PACK>), dim3(p.grid), dim3(SPLITQ ? 512 : 256), lds, st, g, a);
   if (p.units)  // the combine launch needs LDS only for the parked critical-token rows
-    hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ, true>), dim3(p.units), dim3(SPLITQ ? 512 : 256),
-                       (size_t)PG * g.nwin * D * 2, st, g, a);
+    hipLaunchKernelGGL((fwd_pipe_kernel<D, SPLITQ, true, PACK>), dim3(p.units), dim3(SPLITQ ? 512 : 256),
+                       (size_t)PGK * g.nwin * D * 2, st, g, a);
   return check_launch();
 }
 
 int launch_fwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st) {
   const bool splitq = a.n_keep > 32;
-  if (g.d == 128) return splitq ? launch_fwd_pipe_t<128, true>(g, a, st) : launch_fwd_pipe_t<128, false>(g, a, st);
-  return splitq ? launch_fwd_pipe_t<64, true>(g, a, st) : launch_fwd_pipe_t<64, false>(g, a, st);
+  if (fwd_packs(g, a.n_keep)) return g.d == 128 ? launch_fwd_pipe_t<128, false, true>(g, a, st) : launch_fwd_pipe_t<64, false, true>(g, a, st);
+  if (g.d == 128) return splitq ? launch_fwd_pipe_t<128, true, false>(g, a, st) : launch_fwd_pipe_t<128, false, false>(g, a, st);
+  return splitq ? launch_fwd_pipe_t<64, true, false>(g, a, st) : launch_fwd_pipe_t<64, false, false>(g, a, st);
 }
 
 }  // namespace bsa

@@ -54,6 +54,13 @@ CASES = {
     "bm_wan": Workload("mini_wan", 1, 2, 128, "bf16", (8, 8, 12), (4, 4, 4), threshold=0.6, block_major=True),
     "bm_win_split": Workload("win_split", 1, 2, 128, "bf16", (16, 16, 24), (4, 4, 4), threshold=0.7, window=(2, 2, 2), seed=3,
                              block_major=True),
+    # 16 or fewer retained queries per block: a wavefront carries two query blocks.  A split tail with
+    # windows; a block count that is not a multiple of eight (a wavefront with one real and one
+    # missing block, a group with missing wavefronts); a single retained query per block
+    "pack_win_split": Workload("pack_win_split", 1, 4, 128, "bf16", (16, 16, 24), (4, 4, 4), threshold=0.7, keep_ratio=0.25,
+                               window=(2, 2, 2), seed=5),
+    "pack_ragged": Workload("pack_ragged", 1, 5, 64, "bf16", (12, 12, 20), (4, 4, 4), threshold=0.7, keep_ratio=0.25),
+    "pack_keep_one": Workload("pack_keep_one", 1, 2, 128, "bf16", (4, 8, 12), (4, 4, 4), threshold=0.6, keep_ratio=1 / 64),
     # threshold 1: every block selected
     "p_one": Workload("p_one", 1, 1, 64, "bf16", (4, 8, 8), (2, 4, 4), threshold=1.0, keep_ratio=0.5),
 }
