@@ -621,8 +621,11 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
 
 // ------------------------------------------------------------------------------- dQ
 // COMBINE as in the forward: segments of a split unit leave their dQ^T sums in a.part.
-template <int D, bool SPLITQ, bool COMBINE>
+// PACK as in the forward: two query blocks per wavefront when n_keep <= 16.
+template <int D, bool SPLITQ, bool COMBINE, bool PACK>
 __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom g, AttnArgs a) {
+  static_assert(!(PACK && SPLITQ), "packing is for short retained sets");
+  constexpr int PG = PACK ? 2 * bsa::PG : bsa::PG;  // query blocks per workgroup
   using R = BwdRec<D, SPLITQ ? 2 : 1>;
   constexpr int NT = SPLITQ ? 512 : 256;
   constexpr int NB = SPLITQ ? 4 : 2;
@@ -636,7 +639,10 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = lane >> 5, col = lane & 31;
-  const int qb = wave & 3, sub = wave >> 2;
+  const int sub = wave >> 2;
+  const int qb0 = PACK ? 2 * wave : (wave & 3);  // the wavefront's (first) query block within the workgroup
+  const int qb = PACK ? qb0 + (col >> 4) : qb0;  // the lane's
+  constexpr int NOWN = PACK ? 2 : 1;
   constexpr int NW = NT / 64;          // wavefronts
   constexpr int NREG = (D / 32) * 16;  // floats per lane of a partial result: the dQ^T tile
   const int ngroups = (g.N + PG - 1) / PG;
@@ -645,6 +651,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
   else if (!item_of(blockIdx.x, ngroups * g.B * g.H, a.split_S, a.split_n, it)) return;
   const int unit = it.unit;
   const int64_t bh = unit / ngroups;
+  const int i0 = (unit % ngroups) * PG + qb0;
   const int i = (unit % ngroups) * PG + qb;
   const bool valid = i < g.N;
   const int64_t row = bh * g.N + i;
@@ -659,15 +666,21 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
     for (int k = tid; k < PG * W; k += NT) masks[k] = 0u;
   if (tid < 2 * PG) keepbits[tid >> 1][tid & 1] = 0u;
   __syncthreads();
-  if (!COMBINE && valid && sub == 0) {
-    if (g.dense) {
-      for (int w = lane; w < W; w += 64)
-        masks[qb * W + w] = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
-    } else {
-      const int beg = a.q2k_ptr[row], cnt = a.q2k_ptr[row + 1] - beg;
-      for (int t = lane; t < cnt; t += 64) {
-        const int j = a.q2k_idx[beg + t];
-        if ((unsigned)j < (unsigned)g.N) atomicOr(&masks[qb * W + (j >> 5)], 1u << (j & 31));
+  if (!COMBINE && sub == 0) {
+#pragma unroll
+    for (int o2 = 0; o2 < NOWN; ++o2) {  // the wavefront's own list(s)
+      const int ib = i0 + o2, ql = qb0 + o2;
+      if (ib >= g.N) continue;
+      if (g.dense) {
+        for (int w = lane; w < W; w += 64)
+          masks[ql * W + w] = (w * 32 + 32 <= g.N) ? 0xffffffffu : ((1u << (g.N - w * 32)) - 1u);
+      } else {
+        const int64_t rw = bh * g.N + ib;
+        const int beg = a.q2k_ptr[rw], cnt = a.q2k_ptr[rw + 1] - beg;
+        for (int t = lane; t < cnt; t += 64) {
+          const int j = a.q2k_idx[beg + t];
+          if ((unsigned)j < (unsigned)g.N) atomicOr(&masks[ql * W + (j >> 5)], 1u << (j & 31));
+        }
       }
     }
   }
@@ -689,7 +702,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
   };
 
   // Q^T and G^T fragments (B operands) and the row constants, from the query block's record
-  const int qpos = 32 * sub + col;
+  const int qpos = PACK ? (col & 15) : 32 * sub + col;
   int qid = -1, qtok = 0;
   float lse2 = INFINITY, delta = 0.f;
   if (valid && qpos < a.n_keep) {
@@ -753,18 +766,18 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
         for (int r = 0; r < 16; ++r) dq[dt][r] += v[dt * 16 + r];
     }
   }
-  WalkN<PG, 1> walk(masks, W, qb);
+  WalkN<PG, NOWN> walk(masks, W, qb0);
   int issued = 0;
-  uint32_t pending = 0;
+  uint32_t pending = 0;  // two bits per tile in flight: which of the wavefront's lists hold it
   if (!COMBINE) {
     if (it.nseg > 1) walk.restrict_to(it.seg, it.nseg);
 #pragma unroll
     for (int k = 0; k < NB - 1; ++k) {
-      bool mk = false;
+      uint32_t mk = 0;
       const int jb = walk.next(mk);
       if (jb >= 0) {
         issue(jb, k);
-        pending |= (mk ? 1u : 0u) << k;
+        pending |= mk << (2 * k);
         ++issued;
       }
     }
@@ -780,19 +793,22 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
     }
     raw_barrier();
     {
-      bool mn = false;
+      uint32_t mn = 0;
       const int jn = walk.next(mn);
       if (jn >= 0) {
         issue(jn, (t + NB - 1) & (NB - 1));
-        pending |= (mn ? 1u : 0u) << (NB - 1);
+        pending |= mn << (2 * (NB - 1));
         ++issued;
       }
     }
-    const bool mine = pending & 1u;
-    pending >>= 1;
+    const uint32_t mbits = pending & 3u;
+    const bool mine = mbits != 0;
+    pending >>= 2;
     if (mine) {
       const uint8_t* Kb = ring + (t & (NB - 1)) * 2 * TILE;
       const uint8_t* Vb = Kb + TILE;
+      // packed: a tile that is not on this lane's block's list contributes P = 0
+      const float lse_t = (PACK && !((mbits >> (col >> 4)) & 1u)) ? INFINITY : lse2;
       // one key half (32 keys) at a time: 2*DS row fragments (K, V alternating), then 2*DT
       // transposed K fragments; a ring of RING register fragments runs ahead of the MFMAs
       constexpr int RING = 8, NF = 2 * DS + 2 * DT;
@@ -822,7 +838,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c2, -lse2));
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c2, -lse_t));
           s[r] = p * (dp[r] - delta);
         }
         const bf16x8 d0 = d_to_b(s, 0), d1 = d_to_b(s, 1);
@@ -859,13 +875,18 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
   }
   __syncthreads();
   // pruned queries take no part in the forward: zero gradient rows
-  if (valid && !g.dense && sub == 0) {
-    const bool kept = (keepbits[qb][lane >> 5] >> (lane & 31)) & 1u;
-    if (!kept) {
-      const int64_t tok = block_origin(g, i) + koff[lane];
-      const u32x4 z = {0u, 0u, 0u, 0u};
+  if (!g.dense && sub == 0) {
 #pragma unroll
-      for (int q = 0; q < D / 8; ++q) *reinterpret_cast<u32x4*>(dQh + tok * D + 8 * q) = z;
+    for (int o2 = 0; o2 < NOWN; ++o2) {  // the wavefront's own block(s)
+      const int ib = i0 + o2, ql = qb0 + o2;
+      if (ib >= g.N) continue;
+      const bool kept = (keepbits[ql][lane >> 5] >> (lane & 31)) & 1u;
+      if (!kept) {
+        const int64_t tok = block_origin(g, ib) + koff[lane];
+        const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int q = 0; q < D / 8; ++q) *reinterpret_cast<u32x4*>(dQh + tok * D + 8 * q) = z;
+      }
     }
   }
 }
@@ -1280,32 +1301,33 @@ static SplitPlan dkv_plan(const Geom& g) {
 }
 constexpr size_t dkv_part_bytes(int d) { return (size_t)4 * 2 * (d / 32) * 16 * 64 * sizeof(float); }  // per segment
 
-template <int D, int NQT>
+template <int D, int NQT, bool PACK>
 static int launch_bwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
   using R = BwdRec<D, NQT>;
   constexpr bool SPLITQ = NQT == 2;
+  constexpr int PGK = PACK ? 2 * PG : PG;
   const int W = (g.N + 31) / 32;
   if (a.stages & BSA_BWD_PRE)  // LDS: per-row-group partial sums + per-window sums of the fill gradient
     hipLaunchKernelGGL((bwd_pre_pipe_kernel<D, NQT>), dim3(g.rows), dim3(256), (size_t)(256 / (D / 8) + g.nwin) * D * 4, st, g, a);
-  const size_t lds_q = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PG * W * 4;
+  const size_t lds_q = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PGK * W * 4;
   const size_t lds_kv = (size_t)4 * PBK * D * 2 + (size_t)DkvRing<NQT>::NB * R::BYTES + (size_t)2 * W * 4;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_pipe_kernel<D, SPLITQ, false>),
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_pipe_kernel<D, SPLITQ, false, PACK>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q) != hipSuccess ||
       hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_pipe_kernel<D, NQT>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv) != hipSuccess)
     return BSA_ERR_LAUNCH;
   if (a.stages & BSA_BWD_DQ) {
-    const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense);  // the dQ walk is the forward's walk
+    const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense, PACK);  // the dQ walk is the forward's walk
     a.split_S = p.S;
     a.split_n = p.n;
     a.part = reinterpret_cast<float*>(static_cast<uint8_t*>(a.ws) + (size_t)R::BYTES * g.rows);  // behind the records
-    hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ, false>), dim3(p.grid), dim3(SPLITQ ? 512 : 256), lds_q, st, g, a);
+    hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ, false, PACK>), dim3(p.grid), dim3(SPLITQ ? 512 : 256), lds_q, st, g, a);
     if (p.units)
-      hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ, true>), dim3(p.units), dim3(SPLITQ ? 512 : 256), 0, st, g, a);
+      hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ, true, PACK>), dim3(p.units), dim3(SPLITQ ? 512 : 256), 0, st, g, a);
   }
   if (a.stages & BSA_BWD_DKV) {
     const SplitPlan p = dkv_plan(g);
-    const SplitPlan pq = fwd_plan(g, a.n_keep, !g.dense);
+    const SplitPlan pq = fwd_plan(g, a.n_keep, !g.dense, PACK);
     a.kv_split_S = p.S;
     a.kv_split_n = p.n;
     a.kv_part = reinterpret_cast<float*>(static_cast<uint8_t*>(a.ws) + (size_t)R::BYTES * g.rows +
@@ -1318,15 +1340,16 @@ static int launch_bwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
 
 int launch_bwd_pipe(const Geom& g, const AttnArgs& a, hipStream_t st) {
   const bool two = a.n_keep > 32;
-  if (g.d == 128) return two ? launch_bwd_pipe_t<128, 2>(g, a, st) : launch_bwd_pipe_t<128, 1>(g, a, st);
-  return two ? launch_bwd_pipe_t<64, 2>(g, a, st) : launch_bwd_pipe_t<64, 1>(g, a, st);
+  if (fwd_packs(g, a.n_keep)) return g.d == 128 ? launch_bwd_pipe_t<128, 1, true>(g, a, st) : launch_bwd_pipe_t<64, 1, true>(g, a, st);
+  if (g.d == 128) return two ? launch_bwd_pipe_t<128, 2, false>(g, a, st) : launch_bwd_pipe_t<128, 1, false>(g, a, st);
+  return two ? launch_bwd_pipe_t<64, 2, false>(g, a, st) : launch_bwd_pipe_t<64, 1, false>(g, a, st);
 }
 
 size_t bwd_workspace_pipe(const Geom& g, int n_keep) {
   const bool two = n_keep > 32;
   const size_t per_row = g.d == 128 ? (two ? BwdRec<128, 2>::BYTES : BwdRec<128, 1>::BYTES)
                                     : (two ? BwdRec<64, 2>::BYTES : BwdRec<64, 1>::BYTES);
-  const SplitPlan p = fwd_plan(g, n_keep, !g.dense);
+  const SplitPlan p = fwd_plan(g, n_keep, !g.dense, fwd_packs(g, n_keep));
   const size_t partials = (size_t)p.units * p.S * (two ? 8 : 4) * dq_part_regs(g.d) * 64 * sizeof(float);
   const SplitPlan pk = dkv_plan(g);
   return per_row * (size_t)g.rows + partials + (size_t)pk.units * pk.S * dkv_part_bytes(g.d);  // records | dQ partials | dK/dV partials
