@@ -520,7 +520,10 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
   const uint16_t* Oh = static_cast<const uint16_t*>(a.O) + bh * g.L * D;
   const uint16_t* dOh = static_cast<const uint16_t*>(a.dO) + bh * g.L * D;
   const float* Lh = a.LSE_in + bh * g.L;
-  uint8_t* rec = static_cast<uint8_t*>(a.ws) + row * (int64_t)R::BYTES;
+  // a.pack (n_keep <= 16): two query blocks share a record, rows 0..15 the even block's, 16..31 the odd one's
+  const int64_t recno = a.pack ? bh * ((g.N + 1) / 2) + (i >> 1) : row;
+  const int r0 = a.pack ? 16 * (i & 1) : 0, nrows = a.pack ? 16 : R::NQ;
+  uint8_t* rec = static_cast<uint8_t*>(a.ws) + recno * (int64_t)R::BYTES;
   const int origin = block_origin(g, i);
 
   if (tid < PBK) {
@@ -580,8 +583,10 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
     }
   }
 
-  for (int q = rg; q < R::NQ; q += RPP) {
-    const int tok = qtok[q];
+  // a last block without a partner also writes the partner's half of the record: padding rows
+  const int nwrite = (a.pack && (i & 1) == 0 && i + 1 == g.N) ? 32 : nrows;
+  for (int q = rg; q < nwrite; q += RPP) {
+    const int tok = q < nrows ? qtok[q] : -1;
     u32x4 qv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
     float dsum = 0.f;
     if (tok >= 0) {
@@ -607,14 +612,15 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
         dsum += gf[2 * e + 1] * __uint_as_float(ov[e] & 0xffff0000u);
       }
     }
-    const int pos = c ^ swz<D>(q);  // chunk position inside the swizzled row
-    *reinterpret_cast<u32x4*>(rec + R::QC + q * R::RB + pos * 16) = qv;
-    *reinterpret_cast<u32x4*>(rec + R::GC + q * R::RB + pos * 16) = gv;
+    const int rq = r0 + q;             // row of the record
+    const int pos = c ^ swz<D>(rq);    // chunk position inside the swizzled row
+    *reinterpret_cast<u32x4*>(rec + R::QC + rq * R::RB + pos * 16) = qv;
+    *reinterpret_cast<u32x4*>(rec + R::GC + rq * R::RB + pos * 16) = gv;
 #pragma unroll
     for (int msk = 1; msk < CPR; msk <<= 1) dsum += __shfl_xor(dsum, msk);  // the row's CPR lanes
     if (c == 0) {
-      reinterpret_cast<float*>(rec + R::LS)[q] = tok >= 0 ? Lh[tok] * kLog2e : INFINITY;  // padding rows: exp2(x - inf) = 0
-      reinterpret_cast<float*>(rec + R::DL)[q] = dsum;
+      reinterpret_cast<float*>(rec + R::LS)[rq] = tok >= 0 ? Lh[tok] * kLog2e : INFINITY;  // padding rows: exp2(x - inf) = 0
+      reinterpret_cast<float*>(rec + R::DL)[rq] = dsum;
     }
   }
 }
@@ -659,7 +665,9 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
   const uint16_t* Kh = static_cast<const uint16_t*>(a.K) + bh * g.L * D;
   const uint16_t* Vh = static_cast<const uint16_t*>(a.V) + bh * g.L * D;
   uint16_t* dQh = static_cast<uint16_t*>(a.dQ) + bh * g.L * D;
-  const uint8_t* rec = static_cast<const uint8_t*>(a.ws) + row * (int64_t)R::BYTES;
+  // packed: the wavefront's two blocks (i0 even) share one record, and the lane's row in it is its column
+  const uint8_t* rec = static_cast<const uint8_t*>(a.ws) +
+                       (PACK ? bh * ((g.N + 1) / 2) + (i0 >> 1) : row) * (int64_t)R::BYTES;
 
   if (tid < PBK) koff[tid] = intra_offset(g, tid);
   if (!COMBINE)
@@ -703,21 +711,22 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
 
   // Q^T and G^T fragments (B operands) and the row constants, from the query block's record
   const int qpos = PACK ? (col & 15) : 32 * sub + col;
+  const int rrow = PACK ? col : qpos;  // row of the record
   int qid = -1, qtok = 0;
   float lse2 = INFINITY, delta = 0.f;
   if (valid && qpos < a.n_keep) {
     qid = g.dense ? qpos : min(max(a.keep_idx[row * a.n_keep + qpos], 0), PBK - 1);
     qtok = block_origin(g, i) + koff[qid];
     atomicOr(&keepbits[qb][qid >> 5], 1u << (qid & 31));
-    lse2 = reinterpret_cast<const float*>(rec + R::LS)[qpos];
-    delta = reinterpret_cast<const float*>(rec + R::DL)[qpos];
+    lse2 = reinterpret_cast<const float*>(rec + R::LS)[rrow];
+    delta = reinterpret_cast<const float*>(rec + R::DL)[rrow];
   }
   bf16x8 qf[DS], gf[DS];
 #pragma unroll
   for (int s = 0; s < DS; ++s) {
     u32x4 qv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
     if (!COMBINE && qid >= 0) {
-      const int off = qpos * RB + (((2 * s + grp) ^ swz<D>(qpos)) << 4);
+      const int off = rrow * RB + (((2 * s + grp) ^ swz<D>(rrow)) << 4);
       qv = *reinterpret_cast<const u32x4*>(rec + R::QC + off);
       gv = *reinterpret_cast<const u32x4*>(rec + R::GC + off);
     }
@@ -892,17 +901,30 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void bwd_dq_pipe_kernel(Geom
 }
 
 // ------------------------------------------------------------------------------ dK, dV
-struct Walk2 {  // ascending walk over the union of two lists (bit masks in LDS), scalar state
-  const uint32_t* masks;  // [2][W]
+// Ascending walk over the union of the two KV blocks' k2q lists (bit masks in LDS), scalar
+// state.  PACK: the bits are pairs of query blocks (one shared record), and each KV block has
+// two masks: pairs whose even block lists it, pairs whose odd block does.
+template <bool PACK>
+struct Walk2 {
+  const uint32_t* masks;  // [2][W], packed [2][2][W]
   int W, own_list, word, left;
-  uint32_t u, own;
+  uint32_t u, own, own2;
   __device__ inline Walk2(const uint32_t* m, int W_, int own_)
-      : masks(m), W(W_), own_list(own_), word(-1), left(0x7fffffff), u(0), own(0) {}
-  __device__ inline void load() {
-    u = __builtin_amdgcn_readfirstlane(masks[word] | masks[W + word]);
-    own = __builtin_amdgcn_readfirstlane(masks[own_list * W + word]);
+      : masks(m), W(W_), own_list(own_), word(-1), left(0x7fffffff), u(0), own(0), own2(0) {}
+  __device__ inline uint32_t any(int w) const {
+    return PACK ? (masks[w] | masks[W + w] | masks[2 * W + w] | masks[3 * W + w]) : (masks[w] | masks[W + w]);
   }
-  __device__ inline int next(bool& mine) {
+  __device__ inline void load() {
+    u = __builtin_amdgcn_readfirstlane(any(word));
+    if (PACK) {
+      own = __builtin_amdgcn_readfirstlane(masks[2 * own_list * W + word]);
+      own2 = __builtin_amdgcn_readfirstlane(masks[(2 * own_list + 1) * W + word]);
+    } else {
+      own = __builtin_amdgcn_readfirstlane(masks[own_list * W + word]);
+    }
+  }
+  // mine: bit 0 = on this KV block's list (packed: the pair's even block), bit 1 = the pair's odd block
+  __device__ inline int next(uint32_t& mine) {
     if (left <= 0) return -1;
     while (u == 0) {
       if (++word >= W) return -1;
@@ -910,14 +932,14 @@ struct Walk2 {  // ascending walk over the union of two lists (bit masks in LDS)
     }
     const int b = __builtin_ctz(u);
     u &= u - 1;
-    mine = (own >> b) & 1u;
+    mine = ((own >> b) & 1u) | (PACK ? ((own2 >> b) & 1u) << 1 : 0u);
     --left;
     return word * 32 + b;
   }
   // restrict a fresh walk to segment `seg` of `nseg` equal parts of the union
   __device__ inline void restrict_to(int seg, int nseg) {
     int total = 0;
-    for (int w = 0; w < W; ++w) total += __builtin_popcount(__builtin_amdgcn_readfirstlane(masks[w] | masks[W + w]));
+    for (int w = 0; w < W; ++w) total += __builtin_popcount(__builtin_amdgcn_readfirstlane(any(w)));
     int skip = (int)((int64_t)seg * total / nseg);
     left = (int)((int64_t)(seg + 1) * total / nseg) - skip;
     while (++word < W) {
@@ -948,8 +970,9 @@ struct DkvRing {  // record ring of the dK/dV kernel
   static constexpr int PER = NQT == 1 ? 2 : 1;  // records consumed per step
 };
 
-template <int D, int NQT>
+template <int D, int NQT, bool PACK>
 __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a) {
+  static_assert(!PACK || NQT == 1, "packed records hold two blocks of at most 16 retained queries");
   using R = BwdRec<D, NQT>;
   constexpr int NT = 512;
   constexpr int RB = D * 2, CPR = D / 8, TILE = PBK * RB, DT = D / 32, DS = D / 16;
@@ -982,15 +1005,16 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
   const int j = j0 + which;  // this wavefront's KV block; it owns keys 32*half .. +31
   const bool valid = j < g.N;
   const int64_t colrow = bh * g.N + j;
-  const int W = (g.N + 31) / 32;
+  const int nrec = PACK ? (g.N + 1) / 2 : g.N;  // records of a head (packed: one per pair of query blocks)
+  const int W = (nrec + 31) / 32;
   const uint16_t* Kh = static_cast<const uint16_t*>(a.K) + bh * g.L * D;
   const uint16_t* Vh = static_cast<const uint16_t*>(a.V) + bh * g.L * D;
   uint16_t* dKh = static_cast<uint16_t*>(a.dK) + bh * g.L * D;
   uint16_t* dVh = static_cast<uint16_t*>(a.dV) + bh * g.L * D;
-  const uint8_t* ws = static_cast<const uint8_t*>(a.ws) + bh * g.N * (int64_t)R::BYTES;
+  const uint8_t* ws = static_cast<const uint8_t*>(a.ws) + bh * nrec * (int64_t)R::BYTES;
 
   if (tid < PBK) koff[tid] = intra_offset(g, tid);
-  for (int k = tid; k < 2 * W; k += NT) masks[k] = 0u;
+  for (int k = tid; k < (PACK ? 4 : 2) * W; k += NT) masks[k] = 0u;
   __syncthreads();
   if (valid && half == 0 && par == 0) {
     if (g.dense) {
@@ -1000,7 +1024,9 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
       const int beg = a.k2q_ptr[colrow], cnt = a.k2q_ptr[colrow + 1] - beg;
       for (int t = lane; t < cnt; t += 64) {
         const int ib = a.k2q_idx[beg + t];
-        if ((unsigned)ib < (unsigned)g.N) atomicOr(&masks[which * W + (ib >> 5)], 1u << (ib & 31));
+        if ((unsigned)ib >= (unsigned)g.N) continue;
+        if (PACK) atomicOr(&masks[(2 * which + (ib & 1)) * W + (ib >> 6)], 1u << ((ib >> 1) & 31));
+        else atomicOr(&masks[which * W + (ib >> 5)], 1u << (ib & 31));
       }
     }
   }
@@ -1052,17 +1078,17 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
   };
   auto modnb = [](int x) { return x >= NB ? x - NB : x; };
   const uint32_t lds_wave = uniform_lds(ring + wave * 1024), tid16 = tid * 16u;
-  Walk2 walk(masks, W, which);
+  Walk2<PACK> walk(masks, W, which);
   if (it.nseg > 1) walk.restrict_to(it.seg, it.nseg);
   int issued = 0;        // records requested so far (positions of the union walk)
-  uint32_t pending = 0;  // bit k: position PER*s + k is on this wavefront's list
+  uint32_t pending = 0;  // bits 2k, 2k+1: how position PER*s + k is on this wavefront's list (see Walk2::next)
 #pragma unroll
   for (int k = 0; k < NB - PER; ++k) {
-    bool mk = false;
+    uint32_t mk = 0;
     const int ib = walk.next(mk);
     if (ib >= 0) {
       issue(ib, k);
-      pending |= (mk ? 1u : 0u) << k;
+      pending |= mk << (2 * k);
       ++issued;
     }
   }
@@ -1079,10 +1105,10 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
     int dib[PER];  // query block requested for slot sc + NB - PER + k, or -1 (wave-uniform)
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
-      bool mk = false;
+      uint32_t mk = 0;
       dib[k] = walk.next(mk);
       if (dib[k] >= 0) {
-        pending |= (mk ? 1u : 0u) << (NB - PER + k);
+        pending |= mk << (2 * (NB - PER + k));
         ++issued;
       }
     }
@@ -1095,8 +1121,9 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
       else if (NTAIL && wave == 0 && lane < NTAIL) dma16_raw(src, tid16, dst);
     };
     const int kpos = NQT == 1 ? par : 0;
-    const bool mine = (pending >> kpos) & 1u;
-    pending >>= PER;
+    const uint32_t mbits = (pending >> (2 * kpos)) & 3u;
+    const bool mine = mbits != 0;
+    pending >>= 2 * PER;
     constexpr bool SPREAD = NQT == 1;  // (with two query sub-tiles the spread costs registers the kernel does not have)
     if (!SPREAD || !mine) {
 #pragma unroll
@@ -1143,8 +1170,12 @@ __global__ __launch_bounds__(512, 1) void bwd_dkv_pipe_kernel(Geom g, AttnArgs a
       // D layout: lane = key column, register r = query row 32*qt + 8*(r/4) + 4*grp + r%4
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(ls + 32 * qt + 8 * r4 + 4 * grp);
+        f32x4 l4 = *reinterpret_cast<const f32x4*>(ls + 32 * qt + 8 * r4 + 4 * grp);
         const f32x4 d4 = *reinterpret_cast<const f32x4*>(dl + 32 * qt + 8 * r4 + 4 * grp);
+        if (PACK && !((mbits >> (r4 >> 1)) & 1u)) {  // rows 0..15 / 16..31: a block of the pair that does not list this KV block
+#pragma unroll
+          for (int e = 0; e < 4; ++e) l4[e] = INFINITY;
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * r4 + e], c2, -l4[e]));
@@ -1307,20 +1338,24 @@ static int launch_bwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
   constexpr bool SPLITQ = NQT == 2;
   constexpr int PGK = PACK ? 2 * PG : PG;
   const int W = (g.N + 31) / 32;
+  a.pack = PACK ? 1 : 0;
   if (a.stages & BSA_BWD_PRE)  // LDS: per-row-group partial sums + per-window sums of the fill gradient
     hipLaunchKernelGGL((bwd_pre_pipe_kernel<D, NQT>), dim3(g.rows), dim3(256), (size_t)(256 / (D / 8) + g.nwin) * D * 4, st, g, a);
   const size_t lds_q = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PGK * W * 4;
-  const size_t lds_kv = (size_t)4 * PBK * D * 2 + (size_t)DkvRing<NQT>::NB * R::BYTES + (size_t)2 * W * 4;
+  const int nrec_head = PACK ? (g.N + 1) / 2 : g.N;
+  const size_t nrec = (size_t)g.B * g.H * nrec_head;  // records in the workspace
+  const size_t lds_kv = (size_t)4 * PBK * D * 2 + (size_t)DkvRing<NQT>::NB * R::BYTES +
+                        (size_t)(PACK ? 4 : 2) * ((nrec_head + 31) / 32) * 4;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_pipe_kernel<D, SPLITQ, false, PACK>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q) != hipSuccess ||
-      hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_pipe_kernel<D, NQT>),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_pipe_kernel<D, NQT, PACK>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv) != hipSuccess)
     return BSA_ERR_LAUNCH;
   if (a.stages & BSA_BWD_DQ) {
     const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense, PACK);  // the dQ walk is the forward's walk
     a.split_S = p.S;
     a.split_n = p.n;
-    a.part = reinterpret_cast<float*>(static_cast<uint8_t*>(a.ws) + (size_t)R::BYTES * g.rows);  // behind the records
+    a.part = reinterpret_cast<float*>(static_cast<uint8_t*>(a.ws) + (size_t)R::BYTES * nrec);  // behind the records
     hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ, false, PACK>), dim3(p.grid), dim3(SPLITQ ? 512 : 256), lds_q, st, g, a);
     if (p.units)
       hipLaunchKernelGGL((bwd_dq_pipe_kernel<D, SPLITQ, true, PACK>), dim3(p.units), dim3(SPLITQ ? 512 : 256), 0, st, g, a);
@@ -1330,9 +1365,9 @@ static int launch_bwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
     const SplitPlan pq = fwd_plan(g, a.n_keep, !g.dense, PACK);
     a.kv_split_S = p.S;
     a.kv_split_n = p.n;
-    a.kv_part = reinterpret_cast<float*>(static_cast<uint8_t*>(a.ws) + (size_t)R::BYTES * g.rows +
+    a.kv_part = reinterpret_cast<float*>(static_cast<uint8_t*>(a.ws) + (size_t)R::BYTES * nrec +
                                          (size_t)pq.units * pq.S * (SPLITQ ? 8 : 4) * dq_part_regs(D) * 64 * sizeof(float));
-    hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D, NQT>), dim3(p.grid), dim3(512), lds_kv, st, g, a);
+    hipLaunchKernelGGL((bwd_dkv_pipe_kernel<D, NQT, PACK>), dim3(p.grid), dim3(512), lds_kv, st, g, a);
     if (p.units) hipLaunchKernelGGL((bwd_dkv_combine_kernel<D>), dim3(p.units), dim3(256), 0, st, g, a);
   }
   return check_launch();
@@ -1352,7 +1387,8 @@ size_t bwd_workspace_pipe(const Geom& g, int n_keep) {
   const SplitPlan p = fwd_plan(g, n_keep, !g.dense, fwd_packs(g, n_keep));
   const size_t partials = (size_t)p.units * p.S * (two ? 8 : 4) * dq_part_regs(g.d) * 64 * sizeof(float);
   const SplitPlan pk = dkv_plan(g);
-  return per_row * (size_t)g.rows + partials + (size_t)pk.units * pk.S * dkv_part_bytes(g.d);  // records | dQ partials | dK/dV partials
+  const size_t nrec = fwd_packs(g, n_keep) ? (size_t)g.B * g.H * ((g.N + 1) / 2) : (size_t)g.rows;
+  return per_row * nrec + partials + (size_t)pk.units * pk.S * dkv_part_bytes(g.d);  // records | dQ partials | dK/dV partials
 }
 
 size_t fwd_workspace_pipe(const Geom& g, int n_keep) {

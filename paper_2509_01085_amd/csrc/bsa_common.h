@@ -120,6 +120,7 @@ struct AttnArgs {
   void* fwd_ws;
   int kv_split_S, kv_split_n;  // the same for the dK/dV launch
   float* kv_part;
+  int pack;  // backward records hold two query blocks of at most 16 retained queries each
 };
 
 // plain-ALU fp32-accumulate kernels: any supported shape, fp32 or bf16 storage
