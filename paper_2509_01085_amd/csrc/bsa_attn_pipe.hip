@@ -12,6 +12,8 @@
 //                  workgroups per CU: while one waits at its barrier the other multiplies;
 //   n_keep  > 32 : eight wavefronts, two per query block splitting its queries, four tiles
 //                  in the ring, one workgroup per CU (also the dense baseline's shape).
+//   n_keep <= 16 : as the first, but a wavefront carries two query blocks (16 MFMA columns
+//                  each) and the workgroup eight.
 // Token filling (Sec. 3.2.2) happens in the epilogue: the rows of the critical tokens (one per
 // window of the block) are parked in LDS and copied to their windows' pruned positions.
 #include <math.h>
