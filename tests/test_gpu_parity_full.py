@@ -23,7 +23,10 @@ PLAN = {
     "wan1p3b_win": ((4,), 4, 1),
     "hd720p": ((3, 39), 4, 1),
     "long": ((5,), 4, 1),
+    # 16 retained queries per block: two query blocks per wavefront, paired backward records
+    "wan1p3b_r25": ((2,), 4, 1),
 }
+FULL = dict(WORKLOADS, wan1p3b_r25=WORKLOADS["wan1p3b"].replace(name="wan1p3b_r25", keep_ratio=0.25, window=(2, 2, 2)))
 
 
 MAX_LISTERS = 600
@@ -38,7 +41,7 @@ def _sample(rng, n, k, always=()):
 
 @pytest.mark.parametrize("name", list(PLAN))
 def test_full_size_parity(name):
-    wl = WORKLOADS[name]
+    wl = FULL[name]
     heads, n_qb, n_kb = PLAN[name]
     part = U.part_of(wl)
     tok = part.block_tokens()
