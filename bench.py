@@ -174,8 +174,8 @@ def length_sweep(args, torch, B):
     dev = torch.device("cuda:0")
     base = WORKLOADS["wan1p3b_win"]  # the paper's defaults: 4x4x4 blocks, (2,2,2) windows, r = 0.5
     for grid in LENGTH_GRIDS:
-        for p in (0.9, 0.6):
-            wl = base.replace(grid=grid, threshold=p)
+        for p, r in ((0.9, 0.5), (0.6, 0.5), (0.8, 0.25)):
+            wl = base.replace(grid=grid, threshold=p, keep_ratio=r)
             shp = B.Shape(wl.B, wl.H, *wl.grid, *wl.block, wl.d, B.BF16, *wl.window)
             x = make_inputs(wl, torch)
             Q, K, V, dO = x["Q"], x["K"], x["V"], x["dO"]
