@@ -20,6 +20,8 @@ CASES = {
     "mfma_d128": Workload("hand_d128", 1, 2, 128, "bf16", (8, 8, 12), (4, 4, 4), keep_ratio=0.5),
     "mfma_d64_win": Workload("hand_d64", 2, 1, 64, "bf16", (4, 8, 20), (4, 4, 4), keep_ratio=0.5, window=(2, 2, 2)),
     "mfma_r100": Workload("hand_r100", 1, 1, 128, "bf16", (4, 8, 12), (4, 4, 4), keep_ratio=1.0),
+    # 16 retained queries: two query blocks per wavefront and per backward record; 15 blocks, so the last has no partner
+    "mfma_packed": Workload("hand_packed", 1, 2, 128, "bf16", (4, 12, 20), (4, 4, 4), keep_ratio=0.25),
     "generic_f32": Workload("hand_f32", 1, 2, 72, "fp32", (6, 6, 10), (3, 2, 5), keep_ratio=0.4),
 }
 
