@@ -45,19 +45,22 @@ static SelectWs carve(const Geom& g, void* base) {
 size_t select_workspace_bytes(const Geom& g) { return carve(g, nullptr).bytes; }
 
 // ---------------------------------------------------------------- 1. block logits
-constexpr int TI = 32, TJ = 64, KC = 16;
-
+constexpr int TI = 64, TJ = 64, KC = 16;
+// A 64 x 64 tile of scores per workgroup, 4 x 4 per thread (rows i0 + 4 ti .., columns
+// j0 + 4 tj ..): per channel a thread reads 4 + 4 operands from LDS for 16 multiply-adds.
+// Every output is accumulated over the channels in ascending order, multiply and add rounded
+// separately, whatever the tiling.
 __global__ __launch_bounds__(256) void scores_kernel(Geom g, const double* Qbar, const double* Kbar,
                                                      double scale, double* S) {
-  __shared__ double qs[KC][TI + 1];
-  __shared__ double ks[KC][TJ + 1];
+  __shared__ __align__(16) double qs[KC][TI + 2];  // +2: conflict-free staging stores, rows stay 16-byte aligned
+  __shared__ __align__(16) double ks[KC][TJ + 2];
   const int bh = blockIdx.z;
   const int i0 = blockIdx.y * TI, j0 = blockIdx.x * TJ;
   const int tid = threadIdx.x;
-  const int ti = tid / 16, tj = tid % 16;  // outputs: rows i0 + 2*ti + {0,1}, cols j0 + tj + 16*{0..3}
+  const int ti = tid / 16, tj = tid % 16;
   const double* Qh = Qbar + (int64_t)bh * g.N * g.d;
   const double* Kh = Kbar + (int64_t)bh * g.N * g.d;
-  double acc[2][4] = {};
+  double acc[4][4] = {};
   for (int c0 = 0; c0 < g.d; c0 += KC) {
     __syncthreads();
     for (int e = tid; e < TI * KC; e += 256) {
@@ -71,20 +74,23 @@ __global__ __launch_bounds__(256) void scores_kernel(Geom g, const double* Qbar,
     __syncthreads();
     const int kc = min(KC, g.d - c0);
     for (int c = 0; c < kc; ++c) {
-      const double q0 = qs[c][2 * ti], q1 = qs[c][2 * ti + 1];
+      double q[4], k[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const double k = ks[c][tj + 16 * u];
-        acc[0][u] = __dadd_rn(acc[0][u], __dmul_rn(q0, k));
-        acc[1][u] = __dadd_rn(acc[1][u], __dmul_rn(q1, k));
+        q[u] = qs[c][4 * ti + u];
+        k[u] = ks[c][4 * tj + u];
       }
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[a][u] = __dadd_rn(acc[a][u], __dmul_rn(q[a], k[u]));
     }
   }
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < 4; ++a)
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int i = i0 + 2 * ti + a, j = j0 + tj + 16 * u;
+      const int i = i0 + 4 * ti + a, j = j0 + 4 * tj + u;
       if (i < g.N && j < g.N) S[((int64_t)bh * g.N + i) * g.N + j] = __dmul_rn(acc[a][u], scale);
     }
 }
