@@ -145,6 +145,30 @@ __global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const doubl
     for (int w = 1; w < NW; ++w) t = __dadd_rn(t, red[w]);
     return t;
   };
+  // both at once (one pair of barriers): the sum in the same order as block_sum
+  auto block_sum_count = [&](double v, int c, double& vs, int& cs) {
+    v = wave_sum(v);
+    if (NW == 1) {
+      vs = v;
+      cs = c;
+      return;
+    }
+    __syncthreads();
+    if (lane == 0) {
+      red[wave] = v;
+      redc[wave] = c;
+    }
+    __syncthreads();
+    double t = red[0];
+    int tc = redc[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+      t = __dadd_rn(t, red[w]);
+      tc += redc[w];
+    }
+    vs = t;
+    cs = tc;
+  };
   auto block_max = [&](double v) -> double {
 #pragma unroll
     for (int m = 32; m > 0; m >>= 1) v = fmax(v, __shfl_xor(v, m));
@@ -245,8 +269,9 @@ __global__ __launch_bounds__(64 * NW) void row_select_kernel(Geom g, const doubl
           cl += __popcll(__ballot(ge));
         }
       }
-      const double G = block_sum(gl);
-      const int c = block_count(cl);
+      double G;
+      int c;
+      block_sum_count(gl, cl, G, c);
       if (G >= target) {
         lo = cand;
         cnt_lo = c;
