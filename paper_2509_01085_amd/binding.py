@@ -175,7 +175,7 @@ def alloc_kv_lists(shape: Shape, device, transpose: bool = True) -> KvLists:
 def select_kv(shape: Shape, Qbar: torch.Tensor, Kbar: torch.Tensor, threshold: float,
               score_scale: Optional[float] = None, out: Optional[KvLists] = None,
               transpose: bool = True, stat_z: Optional[float] = None) -> KvLists:
-    """stat_z: the standard-normal quantile of Eq. 3 (see stat_quantile); None = plain Eq. 4."""
+    """stat_z: the quantile U(1 - k/n) of Eq. 3, supplied by the caller; None = plain Eq. 4."""
     if out is None:
         out = alloc_kv_lists(shape, Qbar.device, transpose)
     if score_scale is None:
@@ -188,15 +188,6 @@ def select_kv(shape: Shape, Qbar: torch.Tensor, Kbar: torch.Tensor, threshold: f
         st = lib().bsa_select_kv_stat(C.byref(shape.c()), _ptr(Qbar), _ptr(Kbar), threshold, stat_z, score_scale, *tail)
     _check(st, "bsa_select_kv")
     return out
-
-
-def stat_quantile(k: int, n: int) -> float:
-    """U(1 - k/n) of Eq. 3: the standard-normal quantile for k desired blocks of n."""
-    from statistics import NormalDist
-
-    if not 1 <= k <= n:
-        raise ValueError("1 <= k <= n")
-    return float("-inf") if k == n else NormalDist().inv_cdf(1.0 - k / n)
 
 
 def prune_q(shape: Shape, Q: torch.Tensor, keep_ratio: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -380,19 +380,10 @@ __global__ __launch_bounds__(256) void bwd_dkv_generic_kernel(Geom g, AttnArgs a
   }
 }
 
-template <typename K>
-static int set_lds(K kernel, size_t bytes) {
-  if (bytes > 48 * 1024 &&
-      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          (int)bytes) != hipSuccess)
-    return BSA_ERR_LAUNCH;
-  return BSA_OK;
-}
-
 template <typename T>
 static int fwd_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
   const size_t lds = (size_t)((QT + 2 * KT) * (g.d + 1) + QT * (KT + 1)) * 4;
-  if (int rc = set_lds(fwd_generic_kernel<T>, lds)) return rc;
+  if (int rc = allow_dynamic_lds<fwd_generic_kernel<T>>(lds)) return rc;
   hipLaunchKernelGGL(fwd_generic_kernel<T>, dim3(g.rows, (a.n_keep + QT - 1) / QT), dim3(256), lds, st, g, a);
   return check_launch();
 }
@@ -400,10 +391,10 @@ static int fwd_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
 template <typename T>
 static int bwd_t(const Geom& g, const AttnArgs& a, hipStream_t st) {
   GenericWs w = carve(g, a.n_keep, a.ws);
-  if (a.stages & BSA_BWD_PRE) hipLaunchKernelGGL(bwd_pre_generic_kernel<T>, dim3(g.rows), dim3(256), 0, st, g, a, w);
   const size_t lds = (size_t)((2 * QT + 2 * KT) * (g.d + 1) + 2 * QT * (KT + 1)) * 4;
-  if (int rc = set_lds(bwd_dq_generic_kernel<T>, lds)) return rc;
-  if (int rc = set_lds(bwd_dkv_generic_kernel<T>, lds)) return rc;
+  if (int rc = allow_dynamic_lds<bwd_dq_generic_kernel<T>>(lds)) return rc;
+  if (int rc = allow_dynamic_lds<bwd_dkv_generic_kernel<T>>(lds)) return rc;
+  if (a.stages & BSA_BWD_PRE) hipLaunchKernelGGL(bwd_pre_generic_kernel<T>, dim3(g.rows), dim3(256), 0, st, g, a, w);
   if (a.stages & BSA_BWD_DQ) hipLaunchKernelGGL(bwd_dq_generic_kernel<T>, dim3(g.rows, (a.n_keep + QT - 1) / QT), dim3(256), lds, st, g, a, w);
   if (a.stages & BSA_BWD_DKV) hipLaunchKernelGGL(bwd_dkv_generic_kernel<T>, dim3(g.rows, (g.Bk + KT - 1) / KT), dim3(256), lds, st, g, a, w);
   return check_launch();

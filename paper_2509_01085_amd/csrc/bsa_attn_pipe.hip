@@ -378,7 +378,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-      mx = fmaxf(mx, xor32(mx));
+      mx = pair_max(mx);
       const float mtrue = fmaxf(m, mx * c2);  // c2 > 0: the maximum commutes with the scaling
       // (packed: a query whose block has seen no tile yet stays at -inf; the arithmetic below then uses 0)
       const float mnew = (PACK && mtrue == -INFINITY) ? 0.f : mtrue;
@@ -426,7 +426,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
   // epilogue: normalise, store the retained rows, park the rows of the windows' critical tokens
   // (in the tile ring, idle now) for the fill
   uint16_t* cen_rows = reinterpret_cast<uint16_t*>(smem);  // [PG][nwin][D]
-  const float ltot = l + xor32(l);
+  const float ltot = pair_sum(l);
   const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
   const float lse = ltot > 0.f ? (m + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
   __syncthreads();  // every wavefront is done with the ring
@@ -621,7 +621,9 @@ __global__ __launch_bounds__(256) void bwd_pre_pipe_kernel(Geom g, AttnArgs a) {
 #pragma unroll
     for (int msk = 1; msk < CPR; msk <<= 1) dsum += __shfl_xor(dsum, msk);  // the row's CPR lanes
     if (c == 0) {
-      reinterpret_cast<float*>(rec + R::LS)[rq] = tok >= 0 ? Lh[tok] * kLog2e : INFINITY;  // padding rows: exp2(x - inf) = 0
+      // padding rows, and rows whose list was empty (LSE = -inf): +inf, so that exp2(x - inf) = 0
+      const float lse = tok >= 0 ? Lh[tok] : INFINITY;
+      reinterpret_cast<float*>(rec + R::LS)[rq] = lse == -INFINITY ? INFINITY : lse * kLog2e;
       reinterpret_cast<float*>(rec + R::DL)[rq] = dsum;
     }
   }
@@ -1341,18 +1343,15 @@ static int launch_bwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
   constexpr int PGK = PACK ? 2 * PG : PG;
   const int W = (g.N + 31) / 32;
   a.pack = PACK ? 1 : 0;
-  if (a.stages & BSA_BWD_PRE)  // LDS: per-row-group partial sums + per-window sums of the fill gradient
-    hipLaunchKernelGGL((bwd_pre_pipe_kernel<D, NQT>), dim3(g.rows), dim3(256), (size_t)(256 / (D / 8) + g.nwin) * D * 4, st, g, a);
   const size_t lds_q = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PGK * W * 4;
   const int nrec_head = PACK ? (g.N + 1) / 2 : g.N;
   const size_t nrec = (size_t)g.B * g.H * nrec_head;  // records in the workspace
   const size_t lds_kv = (size_t)4 * PBK * D * 2 + (size_t)DkvRing<NQT>::NB * R::BYTES +
                         (size_t)(PACK ? 4 : 2) * ((nrec_head + 31) / 32) * 4;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_pipe_kernel<D, SPLITQ, false, PACK>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q) != hipSuccess ||
-      hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_pipe_kernel<D, NQT, PACK>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv) != hipSuccess)
-    return BSA_ERR_LAUNCH;
+  if (int rc = allow_dynamic_lds<bwd_dq_pipe_kernel<D, SPLITQ, false, PACK>>(lds_q)) return rc;
+  if (int rc = allow_dynamic_lds<bwd_dkv_pipe_kernel<D, NQT, PACK>>(lds_kv)) return rc;
+  if (a.stages & BSA_BWD_PRE)  // LDS: per-row-group partial sums + per-window sums of the fill gradient
+    hipLaunchKernelGGL((bwd_pre_pipe_kernel<D, NQT>), dim3(g.rows), dim3(256), (size_t)(256 / (D / 8) + g.nwin) * D * 4, st, g, a);
   if (a.stages & BSA_BWD_DQ) {
     const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense, PACK);  // the dQ walk is the forward's walk
     a.split_S = p.S;
@@ -1404,11 +1403,8 @@ static int launch_fwd_pipe_t(const Geom& g, AttnArgs a, hipStream_t st) {
   constexpr int PGK = PACK ? 2 * PG : PG;
   const int W = (g.N + 31) / 32;
   const size_t lds = (size_t)(SPLITQ ? 4 : 2) * 2 * PBK * D * 2 + (size_t)PGK * W * 4;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ, false, PACK>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
-      hipFuncSetAttribute(reinterpret_cast<const void*>(fwd_pipe_kernel<D, SPLITQ, true, PACK>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-    return BSA_ERR_LAUNCH;
+  if (int rc = allow_dynamic_lds<fwd_pipe_kernel<D, SPLITQ, false, PACK>>(lds)) return rc;
+  if (int rc = allow_dynamic_lds<fwd_pipe_kernel<D, SPLITQ, true, PACK>>((size_t)PGK * g.nwin * D * 2)) return rc;
   const SplitPlan p = fwd_plan(g, a.n_keep, !g.dense && a.fwd_ws != nullptr, PACK);
   a.split_S = p.S;
   a.split_n = p.n;

@@ -78,6 +78,24 @@ inline int check_launch() {
   return hipGetLastError() == hipSuccess ? BSA_OK : BSA_ERR_LAUNCH;
 }
 
+// Lets `Kernel` be launched with `bytes` of dynamic LDS.  The attribute call is made only when a
+// launch needs more than any earlier one of the same kernel on the same device did, i.e. once per
+// kernel in steady state; callers run it before they launch anything, so a failure leaves the
+// stream untouched.
+template <auto Kernel>
+inline int allow_dynamic_lds(size_t bytes) {
+  constexpr int kMaxDev = 64;
+  static size_t granted[kMaxDev] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return BSA_ERR_LAUNCH;
+  if (bytes <= granted[dev]) return BSA_OK;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)bytes) != hipSuccess)
+    return BSA_ERR_LAUNCH;
+  granted[dev] = bytes;
+  return BSA_OK;
+}
+
 // bf16 <-> fp32 (round to nearest even), bit-level.
 __device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 __device__ inline uint16_t f32_to_bf16(float f) {

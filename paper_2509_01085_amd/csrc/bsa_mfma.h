@@ -10,9 +10,8 @@
 //
 // A D tile becomes the B operand of the next contraction without any shuffle: registers
 // 8h..8h+7 of lane group g hold rows {16h + 8(t/4) + 4g + t%4}, which is read as "k slot
-// (g, t) of k-step h".  The matching A operand must then present the same rows in the same
-// slots, so tiles that play that A role are stored in LDS with their 64 contraction indices
-// permuted by slot_pos(): the 8 indices of one (k-step, lane group) are contiguous 16 bytes.
+// (g, t) of k-step h".  The matching A operand presents the same rows in the same slots through
+// transposed LDS reads (lds_frag_tr below), so no tile is stored permuted.
 #pragma once
 
 #include "bsa_common.h"
@@ -28,11 +27,6 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-
-// Position, inside a row of 64 contraction indices, of index x (see file comment).
-__host__ __device__ constexpr int slot_pos(int x) {
-  return (x & ~15) | (((x >> 2) & 1) << 3) | (((x >> 3) & 1) << 2) | (x & 3);
-}
 
 __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -141,19 +135,16 @@ __device__ inline bf16x8 lds_frag_tr(const uint8_t* p0, const uint8_t* p1) {
   return __builtin_bit_cast(bf16x8, v);
 }
 
-__device__ inline float xor32(float v) { return __shfl_xor(v, 32); }
-
-// Transpose a 4 (rows) x 8 (columns) block of bf16 held as four 16-byte rows; out[c] packs
-// column c's four values (row 0 in the low half of .x).
-__device__ inline void transpose_4x8(const u32x4 (&r)[4], u32x2 (&out)[8]) {
-#pragma unroll
-  for (int m = 0; m < 4; ++m) {
-    const uint32_t a = r[0][m], b = r[1][m], c = r[2][m], d = r[3][m];
-    out[2 * m].x = (a & 0xffffu) | (b << 16);
-    out[2 * m].y = (c & 0xffffu) | (d << 16);
-    out[2 * m + 1].x = (a >> 16) | (b & 0xffff0000u);
-    out[2 * m + 1].y = (c >> 16) | (d & 0xffff0000u);
-  }
+// Reductions over a lane pair (l, l ^ 32): one v_permlane32_swap puts the two halves of the
+// wavefront side by side (r[0] = the low half's values in both halves, r[1] = the high half's),
+// so every lane combines its own value with its partner's without a trip through LDS.
+__device__ inline float pair_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float pair_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 }  // namespace bsa

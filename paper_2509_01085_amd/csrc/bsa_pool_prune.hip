@@ -32,7 +32,6 @@ __device__ inline void unpack(uint32_t w, double& lo, double& hi) {  // ES == 2:
 // intra-block id, in registers.  No LDS.
 template <int ES>
 __global__ __launch_bounds__(64 * kWaves) void pool_kernel(Geom g, const uint8_t* X, double* Xbar) {
-  constexpr int KW = 256 * 4 / 4 / 64;  // words per lane at the largest row (d = 256 fp32): 4
   constexpr int TB = 16;                // token rows loaded ahead of the additions
   __shared__ int koff[256];
   for (int t = threadIdx.x; t < g.Bk; t += 64 * kWaves) koff[t] = intra_offset(g, t);
@@ -45,9 +44,6 @@ __global__ __launch_bounds__(64 * kWaves) void pool_kernel(Geom g, const uint8_t
   const int words = g.d * ES / 4;
   const int nk = (words + 63) / 64;  // words per lane in use
   const uint32_t* base = reinterpret_cast<const uint32_t*>(X) + (bh * g.L + block_origin(g, i)) * (int64_t)words;
-  double acc[KW][2];
-#pragma unroll
-  for (int k = 0; k < KW; ++k) acc[k][0] = acc[k][1] = 0.0;
 #pragma unroll 1
   for (int k = 0; k < nk; ++k) {  // (one pass for d <= 128 bf16 / d <= 64 fp32)
     const int w = lane + 64 * k;
@@ -84,7 +80,6 @@ __global__ __launch_bounds__(64 * kWaves) void pool_kernel(Geom g, const uint8_t
       }
     }
   }
-  (void)acc;
 }
 
 // ------------------------------------------------------------------------------ pruning

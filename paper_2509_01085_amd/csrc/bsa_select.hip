@@ -473,19 +473,17 @@ int launch_select(const Geom& g, const double* Qbar, const double* Kbar, double 
                   int32_t* k2q_idx, int64_t* nnz_dev, void* ws, hipStream_t st) {
   SelectWs w = carve(g, ws);
   const int BH = g.B * g.H;
+  const size_t lds = (size_t)g.N * sizeof(unsigned long long);  // <= 64 KB
+  if (g.N > 4096)
+    if (int rc = allow_dynamic_lds<row_select_kernel<4, 32>>(lds)) return rc;
   hipLaunchKernelGGL(scores_kernel, dim3((g.N + TJ - 1) / TJ, (g.N + TI - 1) / TI, BH), dim3(256), 0, st,
                      g, Qbar, Kbar, score_scale, w.scores);
-  const size_t lds = (size_t)g.N * sizeof(unsigned long long);  // <= 64 KB
   if (g.N <= 1024)
     hipLaunchKernelGGL((row_select_kernel<1, 16>), dim3(g.rows), dim3(64), lds, st, g, w.scores, threshold, stat_z, w.mask, w.cnt);
   else if (g.N <= 4096)
     hipLaunchKernelGGL((row_select_kernel<4, 16>), dim3(g.rows), dim3(256), lds, st, g, w.scores, threshold, stat_z, w.mask, w.cnt);
-  else {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(row_select_kernel<4, 32>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-      return BSA_ERR_LAUNCH;
+  else
     hipLaunchKernelGGL((row_select_kernel<4, 32>), dim3(g.rows), dim3(256), lds, st, g, w.scores, threshold, stat_z, w.mask, w.cnt);
-  }
   hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, w.cnt, g.rows, q2k_ptr, nnz_dev);
   hipLaunchKernelGGL(expand_kernel, dim3((g.rows + 3) / 4), dim3(256), 0, st, g, w.mask, q2k_ptr, q2k_idx);
   if (k2q_ptr) {

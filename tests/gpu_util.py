@@ -12,6 +12,8 @@ from bsa_workloads import Workload, bf16_round, head_inputs, head_tensor
 from oracle import bsa_oracle as o
 from paper_2509_01085_amd import binding as B
 
+import tolerance as T
+
 # Deciding comparisons closer to equality than this (relative to the row's total mass) are
 # within reach of the one non-reproducible step (exp of libm vs the device, summation tree
 # of the scan): such a row may legitimately differ by its boundary block.
@@ -102,63 +104,42 @@ def check_lists_against_oracle(wl: Workload, shp: B.Shape, host: dict, b: int, h
 
 def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     """max |got - ref| / RMS(ref): the plain tolerance metric."""
-    rms = float(np.sqrt(np.mean(np.asarray(ref, dtype=np.float64) ** 2)))
-    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(rms, 1e-30))
+    return T.figures(got, ref)["plain"]
 
 
-BF16_U = 2.0 ** -8  # unit roundoff of bfloat16 (8 significant bits, round to nearest even)
+def record(case: str, where: str, figs: dict) -> None:
+    """Append the parity figures of one comparison to the run's figure log (one JSON line)."""
+    import json
+    import os
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    try:
+        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(root, "gpurun_out", "parity_figures.jsonl"), "a") as f:
+            f.write(json.dumps({"case": case, "where": where, **figs}) + "\n")
+    except OSError:
+        pass
 
 
-def rounding_bounds(xi: dict, part: o.Partition, ix, sm_scale: float, q_blocks=None):
-    """First-order bounds E_X (X in O, dQ, dK, dV), element by element, on what storing
-    the intermediate operands in bfloat16 can do to X.  With u = 2^-8:
-
-      g  (folded upstream gradient) is rounded before it enters a contraction: |dg| <= u |g|
-         hence |d(dP)| <= u |g| |v|^T
-      P  is rounded before P v and P^T g:                  |dP~| <= u P
-      dS = P (dP - delta) is rounded before dS k, dS^T q:  |d(dS)| <= P u |g||v|^T + u |dS|
-
-      E_O  = u P |v|              E_dV = 2u P^T |g|
-      E_dQ = scale |d(dS)| |k|    E_dK = scale |d(dS)|^T |q|
-
-    Q, K, V, dO are exact in both implementations and accumulation is fp32 or better.
-    The rounding of the stored result itself, u |X|, is added by parity_excess()."""
-    u = BF16_U
-    tok = part.block_tokens()
-    X = {k: np.asarray(v, dtype=np.float64) for k, v in xi.items()}
-    E = {k: np.zeros((part.L, X["Q"].shape[1])) for k in ("O", "dQ", "dK", "dV")}
-    for i in (range(part.N) if q_blocks is None else q_blocks):
-        rows = tok[i, ix.keep_idx[i]]
-        keys = tok[ix.q2k_idx[ix.q2k_ptr[i]:ix.q2k_ptr[i + 1]]].reshape(-1)
-        q, k, v = X["Q"][rows], X["K"][keys], X["V"][keys]
-        out, _, P = o.attend_block(q, k, v, sm_scale)
-        g = o.folded_grad(X["dO"], part, ix.keep_idx, i, tok)
-        dS = P * (g @ v.T - (g * out).sum(axis=1, keepdims=True))
-        ddS = u * (P * (np.abs(g) @ np.abs(v).T) + np.abs(dS))
-        eO = u * (P @ np.abs(v))
-        cpos = np.searchsorted(ix.keep_idx[i], part.center_of())  # each token's window center among the retained rows
-        E["O"][tok[i]] = eO[cpos]
-        E["O"][rows] = eO
-        E["dQ"][rows] = sm_scale * (ddS @ np.abs(k))
-        E["dK"][keys] += sm_scale * (ddS.T @ np.abs(q))
-        E["dV"][keys] += 2 * u * (P.T @ np.abs(g))
-    return E
-
-
-def parity_excess(got: np.ndarray, ref: np.ndarray, dtype: str, E: Optional[np.ndarray] = None) -> float:
-    """The parity figure compared with the tolerance (1e-4 for fp32, 2e-2 for bf16).
-
-    fp32: max |got - ref| / RMS(ref).
-    bf16: max (|got - ref| - E - u |ref|) / RMS(ref), E from rounding_bounds(): what is left
-    after the unavoidable effect of bfloat16 storage of operands and of the result must
-    stay below the tolerance."""
-    got = np.asarray(got, dtype=np.float64)
-    rms = max(float(np.sqrt(np.mean(np.asarray(ref, dtype=np.float64) ** 2))), 1e-30)
-    err = np.abs(got - ref)
-    if dtype == "bf16":
-        assert E is not None
-        err = np.maximum(err - E - BF16_U * np.abs(ref), 0.0)
-    return float(err.max() / rms)
+def check_tensors(case: str, where: str, dtype: str, pairs, sigma=None, lse=None) -> dict:
+    """Hold every (name, got, ref) of `pairs` to the criteria of tests/tolerance.py; `sigma`: the
+    operand-rounding model's standard deviations for the bf16 gradients; `lse` = (got, ref).
+    The figures are logged whether or not they pass.  Returns them."""
+    figs, bad = {}, []
+    for name, got, ref in pairs:
+        sg = (sigma or {}).get(name) if dtype == "bf16" and name != "O" else None  # O: no operand term
+        if dtype == "bf16" and name != "O":
+            assert sg is not None, f"no rounding model for {name}"
+        f = T.figures(got, ref, sg)
+        bad += T.failures(name, f, dtype)
+        figs[name] = {k: float(f"{v:.3e}") for k, v in f.items()}
+    if lse is not None:
+        figs["LSE"] = {"abs": float(f"{np.abs(np.asarray(lse[0], dtype=np.float64) - lse[1]).max():.3e}")}
+        if not figs["LSE"]["abs"] <= T.TOL_LSE:
+            bad.append(f"LSE: max-abs {figs['LSE']['abs']:.3e} > {T.TOL_LSE}")
+    record(case, where, figs)
+    assert not bad, (case, where, bad, figs)
+    return figs
 
 
 def o_storage_of(wl: Workload):
@@ -168,30 +149,5 @@ def o_storage_of(wl: Workload):
     return lambda O: bf16_round(np.asarray(O, dtype=np.float32))
 
 
-def tol_of(wl: Workload) -> float:
-    return 1e-4 if wl.dtype == "fp32" else 2e-2
-
-
 def host_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float64).cpu().numpy()
-
-
-def rounding_bounds_kv_block(xi: dict, part: o.Partition, ix, sm_scale: float, j: int):
-    """E_dK, E_dV of rounding_bounds() for the Bk tokens of KV block j alone."""
-    u = BF16_U
-    tok = part.block_tokens()
-    X = {k: np.asarray(v, dtype=np.float64) for k, v in xi.items()}
-    kj, vj = X["K"][tok[j]], X["V"][tok[j]]
-    EK, EV = np.zeros_like(kj), np.zeros_like(vj)
-    for i in ix.k2q_idx[ix.k2q_ptr[j]:ix.k2q_ptr[j + 1]]:
-        rows = tok[i, ix.keep_idx[i]]
-        keys = tok[ix.q2k_idx[ix.q2k_ptr[i]:ix.q2k_ptr[i + 1]]].reshape(-1)
-        q = X["Q"][rows]
-        out, lse, _ = o.attend_block(q, X["K"][keys], X["V"][keys], sm_scale)
-        g = o.folded_grad(X["dO"], part, ix.keep_idx, int(i), tok)
-        Pj = np.exp((q @ kj.T) * sm_scale - lse[:, None])
-        dSj = Pj * (g @ vj.T - (g * out).sum(axis=1, keepdims=True))
-        ddS = u * (Pj * (np.abs(g) @ np.abs(vj).T) + np.abs(dSj))
-        EK += sm_scale * (ddS.T @ np.abs(q))
-        EV += 2 * u * (Pj.T @ np.abs(g))
-    return EK, EV

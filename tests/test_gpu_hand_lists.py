@@ -68,7 +68,7 @@ def test_hand_made_lists(name):
     O, LSE = B.attn_fwd(shp, x["Q"], x["K"], x["V"], lists, keep)
     dQ, dK, dV = B.attn_bwd(shp, x["Q"], x["K"], x["V"], O, LSE, x["dO"], lists, keep)
     torch.cuda.synchronize()
-    tol, tok = U.tol_of(wl), part.block_tokens()
+    tok = part.block_tokens()
     for (b, h), rows in per_head.items():
         xi = head_inputs(wl, b, h)
         hp = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int32)
@@ -80,11 +80,10 @@ def test_hand_made_lists(name):
                                    O_in=U.o_storage_of(wl)(rO))
         kp, ki = o.transpose_csr(hp, hi, N)
         ix = o.HeadResult(None, None, hp, hi, np.asarray(kp), np.asarray(ki), keep_h, 0.0, 0.0)
-        E = U.rounding_bounds(xi, part, ix, scale) if wl.dtype == "bf16" else {}
-        for nm, got, ref in (("O", O, rO), ("dQ", dQ, rdQ), ("dK", dK, rdK), ("dV", dV, rdV)):
-            g = U.host_f64(got[b, h])
-            assert U.parity_excess(g, ref, wl.dtype, E.get(nm)) < tol, (nm, b, h, U.rel_err(g, ref))
-        assert np.abs(U.host_f64(LSE[b, h]) - rLSE).max() < (1e-4 if wl.dtype == "fp32" else 2e-2)
+        sg = U.T.rounding_sigma(xi, part, ix, scale) if wl.dtype == "bf16" else None
+        U.check_tensors("hand " + name, f"b{b} h{h}", wl.dtype,
+                        [(nm, U.host_f64(got[b, h]), ref) for nm, got, ref in (("O", O, rO), ("dQ", dQ, rdQ), ("dK", dK, rdK), ("dV", dV, rdV))],
+                        sigma=sg, lse=(U.host_f64(LSE[b, h]), rLSE))
         # the block nobody lists receives exactly zero gradient
         last = tok[N - 1]
         assert not dK[b, h].float().cpu().numpy()[last].any() and not dV[b, h].float().cpu().numpy()[last].any()

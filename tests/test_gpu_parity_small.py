@@ -1,7 +1,9 @@
 """GPU parity, small shapes: every stage of the HIP path (through the C ABI) against the CPU
 oracle, element by element, on seeded inputs.  Index work (pooled sums are compared as
-doubles, keep lists, CSR, transposed CSR) must be bit-exact; O / LSE / dQ / dK / dV within
-1e-4 (fp32) or 2e-2 (bf16) of the oracle, max-abs relative to the oracle tensor's RMS."""
+doubles, keep lists, CSR, transposed CSR) must be bit-exact; O / LSE / dQ / dK / dV are held to
+the criteria of tests/tolerance.py (fp32: max-abs 1e-4 of the oracle tensor's RMS; bf16: 2e-2
+for O plainly, 5e-3 in RMS for every tensor, and the gradients element by element after the
+bf16 rounding of their own value and of the MFMA operands)."""
 import functools
 from math import sqrt
 
@@ -75,7 +77,7 @@ def run_case(name: str):
     dQ, dK, dV = B.attn_bwd(shp, x["Q"], x["K"], x["V"], O, LSE, x["dO"], lists, keep)
     torch.cuda.synchronize()
     host = U.lists_to_host(shp, lists)
-    ref, bound = {}, {}
+    ref, sigma = {}, {}
     part = U.part_of(wl)
     for b in range(wl.B):
         for h in range(wl.H):
@@ -83,9 +85,9 @@ def run_case(name: str):
             ref[b, h] = o.bsa_head(xi["Q"], xi["K"], xi["V"], xi["dO"], part, wl.threshold, wl.keep_ratio,
                                    o_storage=U.o_storage_of(wl))
             if wl.dtype == "bf16":
-                bound[b, h] = U.rounding_bounds(xi, part, ref[b, h][0], 1 / sqrt(wl.d))
+                sigma[b, h] = U.T.rounding_sigma(xi, part, ref[b, h][0], 1 / sqrt(wl.d))
     return dict(wl=wl, shp=shp, part=part, x=x, Qbar=Qbar, Kbar=Kbar, lists=lists, host=host, keep=keep,
-                O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV, ref=ref, bound=bound)
+                O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV, ref=ref, sigma=sigma, name=name)
 
 
 def heads(r):
@@ -122,24 +124,49 @@ def test_kv_lists_and_transpose_are_bit_exact(name):
 @pytest.mark.parametrize("name", list(CASES))
 def test_forward_matches_oracle(name):
     r = run_case(name)
-    tol = U.tol_of(r["wl"])
     for b, h in heads(r):
         _, O, LSE, *_ = r["ref"][b, h]
-        A = r["bound"].get((b, h), {}).get("O")
-        assert U.parity_excess(U.host_f64(r["O"][b, h]), O, r["wl"].dtype, A) < tol
-        assert np.abs(U.host_f64(r["LSE"][b, h]) - LSE).max() < (1e-4 if r["wl"].dtype == "fp32" else 2e-2)
+        U.check_tensors(name, f"fwd b{b} h{h}", r["wl"].dtype, [("O", U.host_f64(r["O"][b, h]), O)],
+                        lse=(U.host_f64(r["LSE"][b, h]), LSE))
 
 
 @pytest.mark.parametrize("name", list(CASES))
 def test_backward_matches_oracle(name):
     r = run_case(name)
-    tol = U.tol_of(r["wl"])
     for b, h in heads(r):
         _, _, _, dQ, dK, dV = r["ref"][b, h]
-        A = r["bound"].get((b, h), {})
-        for name, ref in (("dQ", dQ), ("dK", dK), ("dV", dV)):
-            got = U.host_f64(r[name][b, h])
-            assert U.parity_excess(got, ref, r["wl"].dtype, A.get(name)) < tol, (name, U.rel_err(got, ref))
+        U.check_tensors(name, f"bwd b{b} h{h}", r["wl"].dtype,
+                        [(t, U.host_f64(r[t][b, h]), ref) for t, ref in (("dQ", dQ), ("dK", dK), ("dV", dV))],
+                        sigma=r["sigma"].get((b, h)))
+
+
+@pytest.mark.parametrize("name", ["tiny", "mini_wan", "mini_wan_r25", "mini_wan_r100", "win_wan", "ragged_bf16"])
+def test_backward_forms_delta_from_the_output_it_is_handed(name):
+    """The backward call receives O (and LSE) as arguments.  Handed a stored O that is visibly not
+    the forward's (the oracle's O plus noise of a quarter of its RMS) and the oracle's LSE, it must
+    reproduce the oracle's backward for that same O: delta = <g, O> comes from the argument."""
+    r = run_case(name)
+    wl, shp, x, part = r["wl"], r["shp"], r["x"], r["part"]
+    store = U.o_storage_of(wl)
+    O2, L2 = torch.empty_like(r["O"]), torch.empty_like(r["LSE"])
+    handed = {}
+    for b, h in heads(r):
+        _, O, LSE, *_ = r["ref"][b, h]
+        rng = np.random.default_rng(1000 + 10 * b + h)
+        handed[b, h] = np.asarray(store(O + 0.25 * sqrt(np.mean(O * O)) * rng.standard_normal(O.shape)), dtype=np.float64)
+        O2[b, h] = torch.from_numpy(handed[b, h]).to(O2.dtype)  # exact: already rounded to the storage type
+        L2[b, h] = torch.from_numpy(LSE).to(L2.dtype)
+    dQ, dK, dV = B.attn_bwd(shp, x["Q"], x["K"], x["V"], O2, L2, x["dO"], r["lists"], r["keep"])
+    torch.cuda.synchronize()
+    scale = 1 / sqrt(wl.d)
+    for b, h in heads(r):
+        xi, ix = head_inputs(wl, b, h), r["ref"][b, h][0]
+        rdQ, rdK, rdV = o.attn_bwd(xi["Q"], xi["K"], xi["V"], xi["dO"], part, ix.q2k_ptr, ix.q2k_idx, ix.keep_idx, scale,
+                                   O_in=handed[b, h])
+        sg = U.T.rounding_sigma(xi, part, ix, scale, own_forward=False, O_in=handed[b, h]) if wl.dtype == "bf16" else None
+        U.check_tensors(name, f"bwd handed-O b{b} h{h}", wl.dtype,
+                        [("dQ", U.host_f64(dQ[b, h]), rdQ), ("dK", U.host_f64(dK[b, h]), rdK), ("dV", U.host_f64(dV[b, h]), rdV)],
+                        sigma=sg)
 
 
 @pytest.mark.parametrize("name", ["tiny_p60", "mini_wan", "ragged_bf16", "win_tiny", "win_wan", "win_ragged"])
@@ -180,15 +207,14 @@ def test_dense_baseline_is_full_attention(name):
     O, LSE = B.dense_attn_fwd(shp, x["Q"], x["K"], x["V"])
     dQ, dK, dV = B.dense_attn_bwd(shp, x["Q"], x["K"], x["V"], O, LSE, x["dO"])
     torch.cuda.synchronize()
-    tol = U.tol_of(wl)
     for b, h in heads(r):
         xi = head_inputs(wl, b, h)
         ix, rO, rL, rdQ, rdK, rdV = o.bsa_head(xi["Q"], xi["K"], xi["V"], xi["dO"], r["part"], 1.0, 1.0,
                                                o_storage=U.o_storage_of(wl))
-        A = U.rounding_bounds(xi, r["part"], ix, 1 / sqrt(wl.d)) if wl.dtype == "bf16" else {}
-        assert np.abs(U.host_f64(LSE[b, h]) - rL).max() < (1e-4 if wl.dtype == "fp32" else 2e-2)
-        for name, got, ref in (("O", O, rO), ("dQ", dQ, rdQ), ("dK", dK, rdK), ("dV", dV, rdV)):
-            assert U.parity_excess(U.host_f64(got[b, h]), ref, wl.dtype, A.get(name)) < tol, name
+        sg = U.T.rounding_sigma(xi, r["part"], ix, 1 / sqrt(wl.d)) if wl.dtype == "bf16" else None
+        U.check_tensors(name + " dense", f"b{b} h{h}", wl.dtype,
+                        [(t, U.host_f64(got[b, h]), ref) for t, got, ref in (("O", O, rO), ("dQ", dQ, rdQ), ("dK", dK, rdK), ("dV", dV, rdV))],
+                        sigma=sg, lse=(U.host_f64(LSE[b, h]), rL))
 
 
 def test_sparse_path_at_threshold_one_equals_dense_path():
@@ -202,7 +228,7 @@ def test_sparse_path_at_threshold_one_equals_dense_path():
     Od, Ld = B.dense_attn_fwd(shp, x["Q"], x["K"], x["V"])
     torch.cuda.synchronize()
     assert U.rel_err(U.host_f64(O), U.host_f64(Od)) < 2e-2
-    assert (LSE - Ld).abs().max().item() < 2e-2
+    assert (LSE - Ld).abs().max().item() < 1e-4
 
 
 @pytest.mark.parametrize("raster,tiled", [("tiny_p60", "bm_tiny"), ("mini_wan", "bm_wan"), ("win_split", "bm_win_split")])

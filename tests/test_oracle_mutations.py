@@ -57,6 +57,31 @@ def make_select_row(strict=False, ascending=False, tie_high=False, off_by_one=Fa
     return select_row
 
 
+def select_row_margin_one_sided(s, p, z=None):
+    """The real selection, but the margin forgets the comparison with c_{k-1}."""
+    sel = SELECT_ROW(s, p, z)
+    if p >= 1.0:
+        return sel
+    s = np.asarray(s, dtype=np.float64)
+    order = np.lexsort((np.arange(s.shape[0]), -s))
+    c = np.cumsum(np.exp(s[order] - s[order[0]]))
+    return o.RowSelection(sel.idx, sel.k, float((c[sel.k - 1] - p * c[-1]) / c[-1]))
+
+
+def select_row_margin_not_relative(s, p, z=None):
+    """The real selection, but the margin is not divided by the row's total mass."""
+    sel = SELECT_ROW(s, p, z)
+    s = np.asarray(s, dtype=np.float64)
+    Z = float(np.sum(np.exp(s - s.max())))
+    return o.RowSelection(sel.idx, sel.k, sel.margin * Z)
+
+
+def prune_q_gap_of_first_block_only(Q, part, r):
+    keep, _ = PRUNE_Q(Q, part, r)
+    first = o.Partition(part.Ct, part.Ch, part.Cw, part.Ct, part.Ch, part.Cw, part.Wt, part.Wh, part.Ww)
+    return keep, PRUNE_Q(np.asarray(Q)[part.block_tokens()[0]], first, r)[1]
+
+
 def transpose_unsorted(ptr, idx, n_cols):
     tptr, tidx = TRANSPOSE(ptr, idx, n_cols)
     out = tidx.copy()
@@ -174,6 +199,10 @@ def stat_threshold_minus(s, z):
 
 
 TRANSPOSE = o.transpose_csr
+SELECT_ROW = o.select_row
+PRUNE_Q = o.prune_q
+MARGIN_PINS = [(pins.test_select_margin_closed_form_and_boundary_nudges, ())]
+GAP_PINS = [(pins.test_prune_gap_is_the_distance_between_the_last_kept_and_the_first_pruned_cosine, ())]
 
 SELECT_PINS = [(pins.test_select_is_minimal_and_maximal_mass_by_brute_force, (p,)) for p in (0.3, 0.5, 0.9)] + [
     (pins.test_select_closed_forms, ()), (pins.test_select_nesting_and_tie_break, ())]
@@ -199,6 +228,9 @@ MUTATIONS = {
     "select: ascending order": ("select_row", make_select_row(ascending=True), SELECT_PINS),
     "select: ties to the higher id": ("select_row", make_select_row(tie_high=True), SELECT_PINS),
     "select: one block too many": ("select_row", make_select_row(off_by_one=True), SELECT_PINS),
+    "select: margin ignores the lower neighbour": ("select_row", select_row_margin_one_sided, MARGIN_PINS),
+    "select: margin not relative to the total mass": ("select_row", select_row_margin_not_relative, MARGIN_PINS),
+    "prune: gap of the first block only": ("prune_q", prune_q_gap_of_first_block_only, GAP_PINS),
     "transpose: lists descending": ("transpose_csr", transpose_unsorted, [(pins.test_transpose_csr_roundtrip_and_counts, ())]),
     "cosine: not normalised": ("cosine_to_center", cosine_unnormalised, PRUNE_PINS),
     "cosine: to the first token": ("cosine_to_center", cosine_to_first_token, PRUNE_PINS),

@@ -143,6 +143,41 @@ def test_select_nesting_and_tie_break():
     assert o.select_row(s, 0.5).idx.tolist() == [1, 2]
 
 
+def test_select_margin_closed_form_and_boundary_nudges():
+    """The margin a row reports is how far its deciding comparisons are from equality, relative
+    to the row's total mass Z: min(c_k - pZ, pZ - c_{k-1}) / Z at the cut k (only the first term
+    when k = 1).  Pinned by the two-block closed form and by moving the threshold itself: the
+    selection must survive p -> p -+ 0.99 margin and must change at p + 1.01 (c_k - pZ)/Z or
+    p - 1.01 (pZ - c_{k-1})/Z."""
+    # two blocks with masses e1 > e2: Z = e1 + e2, c_1 = e1
+    s = np.log(np.array([3.0, 1.0]))
+    for p, k, m in ((0.5, 1, 0.25), (0.7, 1, 0.05), (0.8, 2, 0.05), (0.9, 2, 0.1)):
+        sel = o.select_row(s, p)
+        assert sel.k == k and sel.margin == pytest.approx(m, rel=1e-12), (p, sel)
+    assert o.select_row(s, 1.0).margin == float("inf")
+    rng = np.random.default_rng(5)
+    for trial in range(20):
+        s = rng.normal(size=8) * 1.5
+        p = float(rng.uniform(0.2, 0.95))
+        sel = o.select_row(s, p)
+        order = np.lexsort((np.arange(8), -s))
+        c = np.cumsum(np.exp(s[order] - s[order[0]]))
+        Z = c[-1]
+        up = (c[sel.k - 1] - p * Z) / Z            # room before one more block is needed
+        down = (p * Z - c[sel.k - 2]) / Z if sel.k >= 2 else float("inf")  # room before one block fewer suffices
+        assert sel.margin == pytest.approx(min(up, down), rel=1e-9)
+        for dp in (-0.99 * sel.margin, 0.99 * sel.margin):
+            if 0.0 < p + dp < 1.0:
+                assert o.select_row(s, p + dp).k == sel.k
+        if p + 1.01 * up < 1.0:
+            assert o.select_row(s, p + 1.01 * up).k == sel.k + 1
+        if sel.k >= 2 and p - 1.01 * down > 0.0:
+            assert o.select_row(s, p - 1.01 * down).k == sel.k - 1
+    # select_kv reports the smallest margin of its rows
+    S = rng.normal(size=(6, 8))
+    assert o.select_kv(S, 0.8)[2] == min(o.select_row(S[i], 0.8).margin for i in range(6))
+
+
 def test_select_rejects_bad_threshold():
     for p in (0.0, -0.1, 1.5):
         with pytest.raises(ValueError):
@@ -196,6 +231,26 @@ def test_prune_invariants(r):
             assert cos[i, kept_others].max() <= cos[i, pruned].min()
     if r == 1.0:
         assert np.array_equal(keep, np.tile(np.arange(part.Bk), (part.N, 1)))
+
+
+def test_prune_gap_is_the_distance_between_the_last_kept_and_the_first_pruned_cosine():
+    """prune_q's second result: over all windows, the smallest difference between the first
+    pruned cosine and the last retained one (ascending order, center aside).  Zero exactly when
+    some decision was a tie; positive means every keep list was decided by a strict inequality."""
+    part = tiny_part()
+    x = tiny_inputs()
+    for r in (0.25, 0.5, 0.75):
+        keep, gap = o.prune_q(x["Q"], part, r)
+        cos = o.cosine_to_center(x["Q"], part)
+        want = float("inf")
+        for i in range(part.N):
+            kept = [c for c in keep[i] if c != part.center]
+            pruned = [c for c in range(part.Bk) if c not in keep[i]]
+            want = min(want, cos[i, pruned].min() - cos[i, kept].max())
+        assert gap == pytest.approx(want, abs=0.0) and gap > 0.0
+    assert o.prune_q(np.ones((part.L, 8)), part, 0.25)[1] == 0.0  # identical tokens: every decision a tie
+    assert o.prune_q(x["Q"], part, 1.0)[1] == float("inf")       # nothing pruned: nothing decided
+    assert o.bsa_indices(x["Q"], x["K"], part, 0.9, 0.5).prune_gap == o.prune_q(x["Q"], part, 0.5)[1]
 
 
 def test_prune_identical_tokens_and_zero_vectors():
@@ -490,6 +545,10 @@ def test_stat_quantile_selects_about_k_of_n_normal_scores():
     for k in (20, 200, 1000, 1800):
         tau = o.stat_threshold(s, o.stat_quantile(k, n))
         assert abs(int((s >= tau).sum()) - k) <= 2
+    # tabulated standard-normal quantiles: U(0.9), U(0.975), U(0.5), U(0.1)
+    assert o.stat_quantile(1, 10) == pytest.approx(1.2815515655446004, abs=1e-12)
+    assert o.stat_quantile(1, 40) == pytest.approx(1.959963984540054, abs=1e-12)
+    assert o.stat_quantile(9, 10) == pytest.approx(-1.2815515655446004, abs=1e-12)
     assert o.stat_quantile(n, n) == float("-inf")
     assert abs(o.stat_quantile(n // 2, n)) < 1e-12  # the median: z = 0
     with pytest.raises(ValueError):
