@@ -18,7 +18,8 @@
  *     per block, N = L / Bk blocks, block id = (bt*Nh + bh)*Nw + bw, intra-block id
  *     = (ct*Ch + ch)*Cw + cw.  "rows" = B*H*N (one row per head and query block).
  *   - Ownership: the caller allocates and frees every buffer, including workspaces.
- *     The library keeps no state and never allocates device memory.
+ *     The library never allocates device memory and keeps no state between calls (the one
+ *     built-in scratch buffer, used by bsa_select_kv_static only, carries nothing over).
  *   - Asynchrony: a call only enqueues work on `stream` (a hipStream_t passed as
  *     void*; NULL = the default stream) and returns; it never synchronises.
  *   - Errors: 0 on success, a negative bsa_status otherwise.  All argument checks are
@@ -51,7 +52,8 @@ enum bsa_status {
   BSA_ERR_CAPACITY = -4,    /* index buffer smaller than the worst case rows*N */
   BSA_ERR_DTYPE = -5,       /* shape.dtype is neither BSA_F32 nor BSA_BF16 */
   BSA_ERR_LAUNCH = -6,      /* the HIP runtime reported a launch error */
-  BSA_ERR_WORKSPACE = -7    /* workspace NULL or smaller than the *_workspace_bytes() figure */
+  BSA_ERR_WORKSPACE = -7,   /* workspace NULL or smaller than the *_workspace_bytes() figure */
+  BSA_ERR_STATIC_LIMIT = -8 /* bsa_select_kv_static: the shape needs more than BSA_STATIC_SELECT_BYTES */
 };
 
 typedef struct bsa_shape {
@@ -106,6 +108,26 @@ int bsa_select_kv(const bsa_shape_t* shape, const double* Qbar, const double* Kb
                   int32_t* q2k_ptr, int32_t* q2k_idx, int64_t idx_capacity,
                   int32_t* k2q_ptr, int32_t* k2q_idx, int64_t* nnz_dev,
                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * bsa_select_kv for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * bsa_select_kv, bit for bit, without the workspace: the scratch (block logits, selection bit
+ * masks, counts) lives in a buffer of BSA_STATIC_SELECT_BYTES that is part of the library's
+ * device image, so every GPU the library runs on holds one copy from load until the process
+ * ends.  The call allocates and frees nothing.
+ *   - A shape with bsa_select_workspace_bytes(shape) > BSA_STATIC_SELECT_BYTES is refused with
+ *     BSA_ERR_STATIC_LIMIT before anything is launched (the 33,280-token, 12-head layer needs
+ *     26.4 MB and fits; larger layers use bsa_select_kv with a caller-owned workspace).
+ *   - All calls on one GPU share that GPU's buffer.  Nothing in it has to start at zero (every
+ *     part is written before it is read within a call), but calls that overlap on one GPU, on
+ *     different streams, race on it: keep them on one stream or order them with events.
+ */
+#define BSA_STATIC_SELECT_BYTES (32u << 20)
+int bsa_select_kv_static(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
+                         double threshold, double score_scale,
+                         int32_t* q2k_ptr, int32_t* q2k_idx, int64_t idx_capacity,
+                         int32_t* k2q_ptr, int32_t* k2q_idx, int64_t* nnz_dev, void* stream);
 
 /*
  * The same selection behind the statistical dynamic threshold of Sec. 3.2.3, Eq. 3: per row,

@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 RASTER, BLOCK_MAJOR = 0, 1
 EXPORTS = (
     "bsa_strerror", "bsa_n_keep", "bsa_pool_blocks", "bsa_select_workspace_bytes", "bsa_select_kv",
-    "bsa_select_kv_stat", "bsa_prune_q", "bsa_fwd_workspace_bytes", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd", "bsa_attn_bwd_stages",
+    "bsa_select_kv_stat", "bsa_select_kv_static", "bsa_prune_q", "bsa_fwd_workspace_bytes", "bsa_attn_fwd", "bsa_bwd_workspace_bytes", "bsa_attn_bwd", "bsa_attn_bwd_stages",
     "bsa_dense_bwd_workspace_bytes", "bsa_dense_attn_fwd", "bsa_dense_attn_bwd", "bsa_mfma_probe",
 )
 
@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
         L.bsa_select_kv.argtypes = [P, vp, vp, f64, f64, vp, vp, i64, vp, vp, vp, vp, sz, vp]
         L.bsa_select_kv_stat.restype = C.c_int
         L.bsa_select_kv_stat.argtypes = [P, vp, vp, f64, f64, f64, vp, vp, i64, vp, vp, vp, vp, sz, vp]
+        L.bsa_select_kv_static.restype = C.c_int
+        L.bsa_select_kv_static.argtypes = [P, vp, vp, f64, f64, vp, vp, i64, vp, vp, vp, vp]
         L.bsa_prune_q.restype, L.bsa_prune_q.argtypes = C.c_int, [P, vp, f64, vp, vp]
         L.bsa_attn_fwd.restype = C.c_int
         L.bsa_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp]
@@ -161,7 +163,10 @@ def select_workspace_bytes(shape: Shape) -> int:
     return lib().bsa_select_workspace_bytes(C.byref(shape.c()))
 
 
-def alloc_kv_lists(shape: Shape, device, transpose: bool = True) -> KvLists:
+STATIC_SELECT_BYTES = 32 << 20  # BSA_STATIC_SELECT_BYTES of the header
+
+
+def alloc_kv_lists(shape: Shape, device, transpose: bool = True, workspace: bool = True) -> KvLists:
     cap = shape.rows * shape.N
     i32 = dict(dtype=torch.int32, device=device)
     return KvLists(
@@ -169,7 +174,20 @@ def alloc_kv_lists(shape: Shape, device, transpose: bool = True) -> KvLists:
         torch.empty(shape.rows + 1, **i32) if transpose else None,
         torch.empty(cap, **i32) if transpose else None,
         torch.zeros(1, dtype=torch.int64, device=device),
-        torch.empty(select_workspace_bytes(shape), dtype=torch.uint8, device=device))
+        torch.empty(select_workspace_bytes(shape) if workspace else 0, dtype=torch.uint8, device=device))
+
+
+def select_kv_static(shape: Shape, Qbar: torch.Tensor, Kbar: torch.Tensor, threshold: float, out: KvLists,
+                     score_scale: Optional[float] = None) -> KvLists:
+    """bsa_select_kv_static: the selection with the library's built-in scratch; `out` (lists and
+    the nnz scalar, no workspace needed) comes from the caller, the call allocates nothing."""
+    if score_scale is None:
+        score_scale = 1.0 / sqrt(shape.d)
+    st = lib().bsa_select_kv_static(C.byref(shape.c()), _ptr(Qbar), _ptr(Kbar), threshold, score_scale,
+                                    _ptr(out.q2k_ptr), _ptr(out.q2k_idx), out.q2k_idx.numel(), _ptr(out.k2q_ptr),
+                                    _ptr(out.k2q_idx), _ptr(out.nnz), _stream())
+    _check(st, "bsa_select_kv_static")
+    return out
 
 
 def select_kv(shape: Shape, Qbar: torch.Tensor, Kbar: torch.Tensor, threshold: float,

@@ -71,6 +71,7 @@ const char* bsa_strerror(int status) {
     case BSA_ERR_DTYPE: return "dtype must be BSA_F32 or BSA_BF16";
     case BSA_ERR_LAUNCH: return "HIP launch error";
     case BSA_ERR_WORKSPACE: return "workspace missing or too small";
+    case BSA_ERR_STATIC_LIMIT: return "shape needs more scratch than the library's built-in buffer holds (BSA_STATIC_SELECT_BYTES)";
     default: return "unknown bsa status";
   }
 }
@@ -96,10 +97,12 @@ size_t bsa_select_workspace_bytes(const bsa_shape_t* shape) {
   return select_workspace_bytes(g);
 }
 
+// use_static: the workspace is this device's copy of the library-owned scratch
 static int select_common(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
                          double threshold, double stat_z, double score_scale, int32_t* q2k_ptr,
                          int32_t* q2k_idx, int64_t idx_capacity, int32_t* k2q_ptr, int32_t* k2q_idx,
-                         int64_t* nnz_dev, void* workspace, size_t workspace_bytes, void* stream) {
+                         int64_t* nnz_dev, void* workspace, size_t workspace_bytes, bool use_static,
+                         void* stream) {
   Geom g;
   int rc = make_geom(shape, &g);
   if (rc) return rc;
@@ -108,6 +111,10 @@ static int select_common(const bsa_shape_t* shape, const double* Qbar, const dou
   if (!(threshold > 0.0) || !(threshold <= 1.0)) return BSA_ERR_RANGE;
   if (!std::isfinite(score_scale)) return BSA_ERR_RANGE;
   if (idx_capacity < (int64_t)g.rows * g.N) return BSA_ERR_CAPACITY;
+  if (use_static) {
+    if (select_workspace_bytes(g) > (size_t)BSA_STATIC_SELECT_BYTES) return BSA_ERR_STATIC_LIMIT;
+    if ((rc = static_select_scratch(&workspace, &workspace_bytes)) != BSA_OK) return rc;
+  }
   if (!workspace || workspace_bytes < select_workspace_bytes(g)) return BSA_ERR_WORKSPACE;
   return launch_select(g, Qbar, Kbar, threshold, stat_z, score_scale, q2k_ptr, q2k_idx, k2q_ptr, k2q_idx,
                        nnz_dev, workspace, (hipStream_t)stream);
@@ -118,7 +125,15 @@ int bsa_select_kv(const bsa_shape_t* shape, const double* Qbar, const double* Kb
                   int64_t idx_capacity, int32_t* k2q_ptr, int32_t* k2q_idx, int64_t* nnz_dev,
                   void* workspace, size_t workspace_bytes, void* stream) {
   return select_common(shape, Qbar, Kbar, threshold, (double)NAN, score_scale, q2k_ptr, q2k_idx,
-                       idx_capacity, k2q_ptr, k2q_idx, nnz_dev, workspace, workspace_bytes, stream);
+                       idx_capacity, k2q_ptr, k2q_idx, nnz_dev, workspace, workspace_bytes, false, stream);
+}
+
+int bsa_select_kv_static(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
+                         double threshold, double score_scale, int32_t* q2k_ptr, int32_t* q2k_idx,
+                         int64_t idx_capacity, int32_t* k2q_ptr, int32_t* k2q_idx, int64_t* nnz_dev,
+                         void* stream) {
+  return select_common(shape, Qbar, Kbar, threshold, (double)NAN, score_scale, q2k_ptr, q2k_idx,
+                       idx_capacity, k2q_ptr, k2q_idx, nnz_dev, nullptr, 0, true, stream);
 }
 
 int bsa_select_kv_stat(const bsa_shape_t* shape, const double* Qbar, const double* Kbar,
@@ -127,7 +142,7 @@ int bsa_select_kv_stat(const bsa_shape_t* shape, const double* Qbar, const doubl
                        int64_t* nnz_dev, void* workspace, size_t workspace_bytes, void* stream) {
   if (stat_z != stat_z) return BSA_ERR_RANGE;  // NaN
   return select_common(shape, Qbar, Kbar, threshold, stat_z, score_scale, q2k_ptr, q2k_idx,
-                       idx_capacity, k2q_ptr, k2q_idx, nnz_dev, workspace, workspace_bytes, stream);
+                       idx_capacity, k2q_ptr, k2q_idx, nnz_dev, workspace, workspace_bytes, false, stream);
 }
 
 int bsa_prune_q(const bsa_shape_t* shape, const void* Q, double keep_ratio, int32_t* keep_idx,

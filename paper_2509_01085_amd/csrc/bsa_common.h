@@ -116,6 +116,7 @@ template <> __device__ inline void store_f32<uint16_t>(uint16_t* p, float v) { *
 int launch_pool(const Geom& g, int dtype, const void* X, double* Xbar, hipStream_t st);
 int launch_prune(const Geom& g, int dtype, const void* Q, int window_quota, int32_t* keep_idx, hipStream_t st);
 size_t select_workspace_bytes(const Geom& g);
+int static_select_scratch(void** ptr, size_t* bytes);  // this device's copy of the library-owned selection scratch
 int launch_select(const Geom& g, const double* Qbar, const double* Kbar, double threshold,
                   double stat_z /* Eq. 3 quantile; NaN or -inf: no candidate filter */, double score_scale, int32_t* q2k_ptr, int32_t* q2k_idx, int32_t* k2q_ptr,
                   int32_t* k2q_idx, int64_t* nnz_dev, void* ws, hipStream_t st);

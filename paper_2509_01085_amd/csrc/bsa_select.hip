@@ -44,6 +44,28 @@ static SelectWs carve(const Geom& g, void* base) {
 
 size_t select_workspace_bytes(const Geom& g) { return carve(g, nullptr).bytes; }
 
+// ---- library-owned scratch for callers that cannot allocate (bsa_select_kv_static) ----------
+// One copy per GPU, resident from module load until the process ends.  `scratch` names the
+// array only towards hipGetSymbolAddress: in host code the identifier is a host-side stand-in,
+// not a device address, so everything below that needs the memory uses the looked-up pointer.
+constexpr size_t kStaticScratchBytes = BSA_STATIC_SELECT_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+int static_select_scratch(void** ptr, size_t* bytes) {
+  constexpr int kMaxDev = 64;
+  static void* dev_ptr[kMaxDev] = {};  // each device holds its own copy at its own address
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return BSA_ERR_LAUNCH;
+  if (!dev_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return BSA_ERR_LAUNCH;
+    dev_ptr[dev] = p;
+  }
+  *ptr = dev_ptr[dev];
+  *bytes = kStaticScratchBytes;
+  return BSA_OK;
+}
+
 // ---------------------------------------------------------------- 1. block logits
 constexpr int TI = 64, TJ = 64, KC = 16;
 // A 64 x 64 tile of scores per workgroup, 4 x 4 per thread (rows i0 + 4 ti .., columns

@@ -74,6 +74,17 @@ def test_null_range_capacity_workspace_errors_come_before_any_launch():
     assert sel(kp=None) == -1  # k2q pointers: both or neither
     stat = lambda z, **k: lib.bsa_select_kv_stat(s, k.get("qb", p), p, 0.9, z, 0.125, p, p, k.get("cap", rows_n), p, p, None, p, ws, None)
     assert stat(float("nan")) == -3 and stat(0.5, qb=None) == -1 and stat(float("-inf"), cap=rows_n - 1) == -4
+    # the variant with the library's built-in scratch: same checks, in the same order, and a
+    # shape whose scratch would not fit is refused before anything touches the device
+    stc = lambda sh=s, **k: lib.bsa_select_kv_static(sh, k.get("qb", p), p, k.get("thr", 0.9), 0.125, p, p,
+                                                     k.get("cap", rows_n), k.get("kp", p), p, None, None)
+    assert stc(qb=None) == -1 and stc(thr=0.0) == -3 and stc(cap=rows_n - 1) == -4 and stc(kp=None) == -1
+    hd = B.Shape(1, 40, 20, 44, 80, 4, 4, 4, 128, B.BF16)
+    assert B.select_workspace_bytes(hd) > B.STATIC_SELECT_BYTES
+    assert stc(C.byref(hd.c()), cap=hd.rows * hd.N) == -8
+    assert b"built-in" in lib.bsa_strerror(-8)
+    wan = B.Shape(1, 12, 20, 32, 52, 4, 4, 4, 128, B.BF16)
+    assert B.select_workspace_bytes(wan) <= B.STATIC_SELECT_BYTES
     assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 0, 0.125, p, p, None, 0, None) == -3
     assert lib.bsa_attn_fwd(s, p, p, p, p, p, p, 33, 0.125, p, p, None, 0, None) == -3
     assert lib.bsa_attn_fwd(s, p, p, None, p, p, p, 16, 0.125, p, p, None, 0, None) == -1
