@@ -341,9 +341,10 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
     if (mine) {
       // 64 keys x this wavefront's 32 queries.  The 4*DS A fragments of the tile (K rows for
       // both key halves, then V^T) are read from LDS through a ring of RING register
-      // fragments, RING MFMAs ahead of their use.  Matrix and vector instructions share the
-      // register-file bandwidth on this chip and barely co-execute (measured), so the code
-      // keeps the vector work per tile minimal rather than trying to hide it.
+      // fragments, RING MFMAs ahead of their use.  Matrix, vector and LDS instructions of a
+      // SIMD co-execute only in part on this chip (measured: the tile's mix keeps the matrix
+      // core at most 55 % busy with two wavefronts that never wait), and the LDS -> MFMA chain is
+      // the critical path of a tile, so the vector work per tile is kept minimal.
       const uint8_t* Kb = ring + (t & (NB - 1)) * 2 * TILE;
       const uint8_t* Vb = Kb + TILE;
       constexpr int RING = 8, NF = 2 * DS + 4 * DT;
