@@ -2,7 +2,7 @@
 // gfx950, within one wavefront and across two wavefronts of a SIMD, and at what issue rates?
 // Every loop body is one inline-asm block, so the instruction order is exactly what is written.
 // One workgroup per CU; 256 threads = one wavefront per SIMD, 512 = two (wavefronts 0-3 run the
-// first body, 4-7 the second).  Times are converted to cycles at 2.4 GHz.
+// first body, 4-7 the second), 768 and 1024 = three and four.  Times are converted to cycles at 2.4 GHz.
 //   hipcc --offload-arch=gfx950 -O3 -o /tmp/mfma_valu_coexec mfma_valu_coexec.hip && /tmp/mfma_valu_coexec
 #include <hip/hip_runtime.h>
 
@@ -122,6 +122,14 @@ int main() {
   run<M_MIX, M_MIX, 8>("4 x (mfma, mix) | 4 x (mfma, mix)", d);
   run<M_DS_MIX, M_DS_MIX, 8>("4 x (mfma, ds_read, mix) | the same", d);
   run<M_DS_FMAC4, M_DS_FMAC4, 8>("4 x (mfma, ds_read, 4 v_fmac) | the same", d);
+  printf("three and four wavefronts per SIMD, all running the same body\n");
+  run<M4, M4, 12>("3 x 4 mfma", d);
+  run<M_MIX, M_MIX, 12>("3 x 4 x (mfma, mix)", d);
+  run<M_DS_MIX, M_DS_MIX, 12>("3 x 4 x (mfma, ds_read, mix)", d);
+  run<M_DS_FMAC4, M_DS_FMAC4, 12>("3 x 4 x (mfma, ds_read, 4 v_fmac)", d);
+  run<M_MIX, M_MIX, 16>("4 x 4 x (mfma, mix)", d);
+  run<M_DS_MIX, M_DS_MIX, 16>("4 x 4 x (mfma, ds_read, mix)", d);
+  run<M_DS_FMAC4, M_DS_FMAC4, 16>("4 x 4 x (mfma, ds_read, 4 v_fmac)", d);
   printf("status %s\n", hipGetErrorString(hipDeviceSynchronize()));
   return 0;
 }
