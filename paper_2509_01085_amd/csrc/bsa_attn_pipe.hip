@@ -343,7 +343,7 @@ __global__ __launch_bounds__(SPLITQ ? 512 : 256, 2) void fwd_pipe_kernel(Geom g,
       // both key halves, then V^T) are read from LDS through a ring of RING register
       // fragments, RING MFMAs ahead of their use.  Matrix, vector and LDS instructions of a
       // SIMD co-execute only in part on this chip (measured: the tile's mix keeps the matrix
-      // core at most 55 % busy with two wavefronts that never wait), and the LDS -> MFMA chain is
+      // core at most 62 % busy with two wavefronts that never wait), and the LDS -> MFMA chain is
       // the critical path of a tile, so the vector work per tile is kept minimal.
       const uint8_t* Kb = ring + (t & (NB - 1)) * 2 * TILE;
       const uint8_t* Vb = Kb + TILE;

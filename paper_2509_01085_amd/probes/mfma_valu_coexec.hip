@@ -31,8 +31,11 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 // softmax-like mix for two score registers: 1 max3, 2 fmac, 2 exp, 2 add, 1 convert = 8 instructions
 #define SM2a MAX3(4, 5) FMAC(6) FMAC(7) EXP(8) EXP(9) ADD(6) ADD(7) CVT(4, 5)
 #define SM2b MAX3(6, 7) FMAC(8) FMAC(9) EXP(4) EXP(5) ADD(8) ADD(9) CVT(6, 7)
+// the attention tile's own ratio: one score register per MFMA (1 max3, 1 fmac, 1 exp, 2 add, 1 convert = 6 instructions)
+#define SM1a MAX3(4, 5) FMAC(6) EXP(8) ADD(6) ADD(7) CVT(4, 5)
+#define SM1b MAX3(6, 7) FMAC(8) EXP(4) ADD(8) ADD(9) CVT(6, 7)
 
-enum { M4, M1CHAIN, FMA32, FMAC32, EXP16, DS8, M_DS2, M_FMAC8, M_FMAC4, M4_THEN_FMAC32, MIX32, M_MIX, M_DS_MIX, M_DS_FMAC4 };
+enum { M4, M1CHAIN, FMA32, FMAC32, EXP16, DS8, M_DS2, M_FMAC8, M_FMAC4, M4_THEN_FMAC32, MIX32, M_MIX, M_DS_MIX, M_DS_FMAC4, M_DS_TILE, TILE_PHASES };
 
 template <int MODE>
 __device__ __forceinline__ void body(f32x16& c0, f32x16& c1, f32x16& c2, f32x16& c3, f32x4 a, f32x4 b, float& v0, float& v1,
@@ -50,6 +53,9 @@ __device__ __forceinline__ void body(f32x16& c0, f32x16& c1, f32x16& c2, f32x16&
   if (MODE == MIX32) BODY(SM2a SM2b SM2a SM2b);
   if (MODE == M_MIX) BODY(MF(0) SM2a MF(1) SM2b MF(2) SM2a MF(3) SM2b);
   if (MODE == M_DS_MIX) BODY(MF(0) DSR(10) SM2a MF(1) DSR2(11) SM2b MF(2) DSR(10) SM2a MF(3) DSR2(11) SM2b WAITL);
+  if (MODE == M_DS_TILE) BODY(MF(0) DSR(10) SM1a MF(1) DSR2(11) SM1b MF(2) DSR(10) SM1a MF(3) DSR2(11) SM1b WAITL);
+  // the same work in the kernels' order: the MFMAs with their LDS reads first, then the vector block
+  if (MODE == TILE_PHASES) BODY(MF(0) DSR(10) MF(1) DSR2(11) MF(2) DSR(10) MF(3) DSR2(11) SM1a SM1b SM1a SM1b WAITL);
   if (MODE == M_DS_FMAC4) BODY(MF(0) DSR(10) X4a(FMAC) MF(1) DSR2(11) X4b(FMAC) MF(2) DSR(10) X4a(FMAC) MF(3) DSR2(11) X4b(FMAC) WAITL);
 }
 
@@ -122,7 +128,14 @@ int main() {
   run<M_MIX, M_MIX, 8>("4 x (mfma, mix) | 4 x (mfma, mix)", d);
   run<M_DS_MIX, M_DS_MIX, 8>("4 x (mfma, ds_read, mix) | the same", d);
   run<M_DS_FMAC4, M_DS_FMAC4, 8>("4 x (mfma, ds_read, 4 v_fmac) | the same", d);
+  run<M_DS_TILE, M_DS_TILE, 4>("one wavefront: 4 x (mfma, ds_read, 6-valu tile mix)", d);
+  run<TILE_PHASES, TILE_PHASES, 4>("one wavefront: 4 x (mfma, ds_read), then 24 valu", d);
+  run<M_DS_TILE, M_DS_TILE, 8>("4 x (mfma, ds_read, 6-valu tile mix) | the same", d);
+  run<TILE_PHASES, TILE_PHASES, 8>("4 x (mfma, ds_read), then 24 valu | the same", d);
   printf("three and four wavefronts per SIMD, all running the same body\n");
+  run<M_DS_TILE, M_DS_TILE, 12>("3 x 4 x (mfma, ds_read, 6-valu tile mix)", d);
+  run<TILE_PHASES, TILE_PHASES, 12>("3 x (4 x (mfma, ds_read), then 24 valu)", d);
+
   run<M4, M4, 12>("3 x 4 mfma", d);
   run<M_MIX, M_MIX, 12>("3 x 4 x (mfma, mix)", d);
   run<M_DS_MIX, M_DS_MIX, 12>("3 x 4 x (mfma, ds_read, mix)", d);
