@@ -21,7 +21,8 @@
  *     The library never allocates device memory and keeps no state between calls (the one
  *     built-in scratch buffer, used by bsa_select_kv_static only, carries nothing over).
  *   - Asynchrony: a call only enqueues work on `stream` (a hipStream_t passed as
- *     void*; NULL = the default stream) and returns; it never synchronises.
+ *     void*; NULL = the default stream) and returns; it never synchronises, so a sequence
+ *     of calls can be recorded into a HIP graph once every kernel has run once eagerly.
  *   - Errors: 0 on success, a negative bsa_status otherwise.  All argument checks are
  *     done on the host before anything is launched; a failed call launches nothing.
  *   - Determinism: equal inputs give bit-identical outputs (no floating-point atomics).
